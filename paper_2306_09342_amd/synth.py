@@ -1,0 +1,104 @@
+"""Seeded synthetic inputs for the reversible-stack backward path.
+
+This module only draws random arrays and places them in the packed parameter
+vector; it holds none of the method's arithmetic, so both the CPU oracle's
+tests and the HIP path's tests/bench may feed from it.  The workloads stand in
+for the paper's 224x224 image-classification batches (Rev-ViT shapes) and its
+text-classification batches (Rev-RoBERTa shape): only the shapes matter for the
+backward path, no dataset item is reproduced.
+
+Recipe (all configs): X ~ N(0,1) [B,T,D], copied to both residual streams;
+every weight matrix truncated-normal(0, 0.02) cut at +-2 sigma by rejection;
+LayerNorm gamma = 1, beta = 0; linear biases 0; dY1, dY2 ~ N(0,1) independent.
+``perturb=True`` (parity tests only) additionally draws non-trivial gammas,
+betas and biases so that a dropped bias or affine term cannot hide.
+In bf16 mode every value is rounded (nearest-even) onto the bf16 grid at
+generation time, so both consumers read identical, exactly representable data.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# name -> (n_blocks, d_model, n_heads, d_mlp, seq_len, batch, mode)
+CONFIGS = {
+    "tiny": dict(n_blocks=4, d_model=64, n_heads=2, d_mlp=256, seq_len=16, batch=4, mode="fp32"),
+    "vit_s": dict(n_blocks=12, d_model=384, n_heads=6, d_mlp=1536, seq_len=197, batch=128, mode="bf16"),
+    "vit_b": dict(n_blocks=12, d_model=768, n_heads=12, d_mlp=3072, seq_len=197, batch=64, mode="bf16"),
+    "roberta_base": dict(n_blocks=12, d_model=768, n_heads=12, d_mlp=3072, seq_len=512, batch=32, mode="bf16"),
+    "vit_h": dict(n_blocks=32, d_model=1280, n_heads=16, d_mlp=5120, seq_len=257, batch=32, mode="bf16"),
+}
+
+# Per-block tensors of the packed parameter vector, in storage order.
+# Linear weights are [out_features, in_features], row-major.
+def block_tensors(d_model: int, d_mlp: int):
+    D, Dm = d_model, d_mlp
+    return [
+        ("ln1_g", (D,)), ("ln1_b", (D,)),
+        ("w_qkv", (3 * D, D)), ("b_qkv", (3 * D,)),
+        ("w_proj", (D, D)), ("b_proj", (D,)),
+        ("ln2_g", (D,)), ("ln2_b", (D,)),
+        ("w_fc1", (Dm, D)), ("b_fc1", (Dm,)),
+        ("w_fc2", (D, Dm)), ("b_fc2", (D,)),
+    ]
+
+
+def params_per_block(d_model: int, d_mlp: int) -> int:
+    return sum(int(np.prod(s)) for _, s in block_tensors(d_model, d_mlp))
+
+
+def to_bf16_grid(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bf16-representable float32 (ties to even)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    u = (u + 0x7FFF + lsb) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def _trunc_normal(rng: np.random.Generator, shape, std: float) -> np.ndarray:
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.float64)
+    filled = 0
+    while filled < n:
+        draw = rng.standard_normal(int((n - filled) * 1.1) + 16)
+        draw = draw[np.abs(draw) <= 2.0]
+        take = min(draw.size, n - filled)
+        out[filled:filled + take] = draw[:take]
+        filled += take
+    return (out * std).reshape(shape)
+
+
+def make_params(cfg: dict, seed: int = 0, perturb: bool = False) -> np.ndarray:
+    """Packed float32 parameter vector for the whole stack."""
+    D, Dm, N = cfg["d_model"], cfg["d_mlp"], cfg["n_blocks"]
+    per = params_per_block(D, Dm)
+    flat = np.empty(N * per, dtype=np.float32)
+    for blk in range(N):
+        off = blk * per
+        for tid, (name, shape) in enumerate(block_tensors(D, Dm)):
+            rng = np.random.default_rng([seed, 1000 + blk, tid])
+            n = int(np.prod(shape))
+            if name.startswith("w_"):
+                v = _trunc_normal(rng, shape, 0.02)
+            elif name.endswith("_g"):
+                v = 1.0 + (0.1 * rng.standard_normal(shape) if perturb else np.zeros(shape))
+            elif name.startswith("ln"):
+                v = 0.1 * rng.standard_normal(shape) if perturb else np.zeros(shape)
+            else:
+                v = 0.02 * rng.standard_normal(shape) if perturb else np.zeros(shape)
+            flat[off:off + n] = np.asarray(v, dtype=np.float32).ravel()
+            off += n
+    if cfg.get("mode", "fp32") == "bf16":
+        flat = to_bf16_grid(flat)
+    return flat
+
+
+def make_inputs(cfg: dict, seed: int = 0, batch: int | None = None):
+    """Returns (X, dY1, dY2), each float32 [B, T, D]; X feeds both streams."""
+    B = cfg["batch"] if batch is None else batch
+    T, D = cfg["seq_len"], cfg["d_model"]
+    out = []
+    for tid in range(3):
+        rng = np.random.default_rng([seed, 7, tid])
+        out.append(rng.standard_normal((B, T, D), dtype=np.float32))
+    return tuple(out)
