@@ -1,0 +1,180 @@
+/*
+ * rev_stack.h -- C ABI of the reversible transformer stack on MI355X (gfx950).
+ *
+ * One block of the stack is the two-stream reversible map of the paper's Eq. 1
+ * (Sec. 3.1), written here with X/Y names (I1->X2, I2->X1, O2->Y1, O1->Y2):
+ *
+ *      Y1 = X1 + F(X2)          F(x) = Proj(MHA(LN1(x)))      attention branch
+ *      Y2 = X2 + G(Y1)          G(x) = fc2(gelu(fc1(LN2(x)))) MLP branch   (Sec. 3.2)
+ *
+ * and its inverse (Sec. 3.1, one call of F and one of G):
+ *
+ *      X2 = Y2 - G(Y1)          X1 = Y1 - F(X2)
+ *
+ * Readings the paper leaves open: LayerNorm sits inside each branch (pre-LN),
+ * uses the biased variance and eps = cfg.ln_eps; attention is softmax(q k^T /
+ * sqrt(head_dim)) v with no mask and no dropout; GELU is the exact erf form;
+ * every linear map has a bias.
+ *
+ * All pointers except `cfg` are DEVICE pointers owned by the caller; the library
+ * allocates no device memory, frees none, and keeps no state between calls
+ * except a pool of HIP events.  Every call only enqueues work and returns; on
+ * return the work is ordered before anything enqueued later on the stream the
+ * call was given (for the PaReprop entry: on `stream_grad`).  Inputs are never
+ * written.  Outputs and the workspace are fully overwritten; they must not
+ * overlap each other or the inputs.  Concurrent calls must use different
+ * workspaces.
+ *
+ * Layouts.  Activations and cotangents X1, X2, Y1, Y2, dY1, dY2, dX1, dX2 are
+ * float32, row-major [batch, seq_len, d_model] (token-major, features
+ * contiguous) in BOTH modes.  `params` is one packed vector, block after block,
+ * each block holding, in this order (linear weights are [out, in] row-major;
+ * the rows of w_qkv are ordered q | k | v, then head, then head_dim):
+ *
+ *      ln1_g[D] ln1_b[D] w_qkv[3D,D] b_qkv[3D] w_proj[D,D] b_proj[D]
+ *      ln2_g[D] ln2_b[D] w_fc1[Dm,D] b_fc1[Dm] w_fc2[D,Dm] b_fc2[D]
+ *
+ * Element type of `params`: float32 in REV_MODE_FP32, bfloat16 in
+ * REV_MODE_BF16.  `dparams` has the same layout, is always float32 and is
+ * overwritten (not accumulated into).
+ *
+ * Modes.  REV_MODE_FP32: all storage and arithmetic float32.  REV_MODE_BF16:
+ * parameters and the per-block activations held in the workspace are bf16,
+ * the dense contractions run on bf16 matrix cores with float32 accumulation;
+ * residual streams, cotangent streams, LayerNorm statistics, softmax
+ * statistics and all parameter gradients stay float32.
+ *
+ * Limits (anything else returns REV_EINVAL before any work is enqueued):
+ * all six sizes positive; d_model % n_heads == 0; d_model % 8 == 0;
+ * d_mlp % 8 == 0; head_dim % 8 == 0 and head_dim <= 128; d_model <= 8192;
+ * d_mlp <= 32768; batch*seq_len < 2^24.
+ *
+ * Errors.  Every int-returning call returns REV_OK (0) or a negative code; the
+ * text of the last failure on the calling thread is returned by
+ * rev_last_error().  Nothing throws or aborts across this boundary.
+ */
+#ifndef REV_STACK_H
+#define REV_STACK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define REV_MODE_FP32 0
+#define REV_MODE_BF16 1
+
+#define REV_OK          0
+#define REV_EINVAL     -1   /* null pointer, bad size, unsupported shape or mode */
+#define REV_EWORKSPACE -2   /* workspace smaller than rev_stack_workspace_bytes  */
+#define REV_EHIP       -3   /* a HIP runtime call failed                          */
+
+typedef struct rev_cfg {
+    int32_t n_blocks;   /* N: number of reversible blocks                    */
+    int32_t d_model;    /* D: width of each residual stream                  */
+    int32_t n_heads;    /* H: attention heads, head_dim = D / H              */
+    int32_t d_mlp;      /* Dm: hidden width of the MLP branch                */
+    int32_t seq_len;    /* T: tokens per sample                              */
+    int32_t batch;      /* B: samples                                        */
+    int32_t mode;       /* REV_MODE_FP32 or REV_MODE_BF16                    */
+    float   ln_eps;     /* LayerNorm epsilon (the paper is silent; 1e-6)     */
+} rev_cfg;
+
+/* Validates cfg; REV_OK or REV_EINVAL.  Host only, touches no GPU. */
+int rev_stack_check_cfg(const rev_cfg* cfg);
+
+/* Number of elements of the packed parameter vector (N * per-block count), or
+ * a negative error code.  Host only. */
+int64_t rev_stack_param_count(const rev_cfg* cfg);
+
+/* Element offset of tensor `tensor` (0..11 in the order listed above) of block
+ * `block` inside the packed vector, and its element count in *count (nullable).
+ * Negative error code on bad arguments.  Host only. */
+int64_t rev_stack_param_offset(const rev_cfg* cfg, int32_t block, int32_t tensor, int64_t* count);
+
+/* Bytes of device workspace any of the three entry points below needs for cfg
+ * (one size covers all; a multiple of 256).  Negative error code on bad cfg.
+ * Holds: two activation slots (the per-block intermediates a gradient step
+ * consumes; the second slot is what lets block i-1 be recomputed while block i
+ * is still being differentiated, Sec. 3.2/3.3), a ring of three residual-stream
+ * levels, two cotangent levels, gradient temporaries, transposed weight copies
+ * and the partial sums of the deterministic reductions.  Host only. */
+int64_t rev_stack_workspace_bytes(const rev_cfg* cfg);
+
+/* Forward map of the whole stack (Eq. 1 applied N times); stores no
+ * activations beyond Y1, Y2.  X1, X2 in; Y1, Y2 out (float32 [B,T,D]).
+ * `stream` is a hipStream_t (NULL = the default stream). */
+int rev_stack_forward(const rev_cfg* cfg, const void* params,
+                      const float* X1, const float* X2, float* Y1, float* Y2,
+                      void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Reversible backpropagation, sequential schedule ("Reprop", Sec. 3.2): for
+ * block N down to 1, on one stream: recompute the block's inputs and
+ * intermediates from its outputs (the inverse above), then apply the block's
+ * transposed Jacobian to the incoming cotangents.
+ *   in : params; Y1, Y2 = outputs of the last block; dY1, dY2 = their cotangents
+ *   out: dX1, dX2 = cotangents of the stack inputs; dparams = gradient of every
+ *        parameter (float32, packed like params, overwritten);
+ *        X1_out, X2_out (nullable) = the reconstructed stack inputs. */
+int rev_stack_backward_reprop(const rev_cfg* cfg, const void* params,
+                              const float* Y1, const float* Y2,
+                              const float* dY1, const float* dY2,
+                              float* dX1, float* dX2,
+                              float* X1_out, float* X2_out, float* dparams,
+                              void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Same inputs, outputs and results -- bit for bit -- as
+ * rev_stack_backward_reprop, under the parallel schedule ("PaReprop", Sec. 3.3,
+ * Fig. 3 bottom row): the recomputation chain R_N, R_{N-1}, ... runs on
+ * `stream_recompute`, the gradient chain V_N, V_{N-1}, ... on `stream_grad`;
+ * V_i waits for R_i, and R_{i-2} waits for V_i (which frees the activation
+ * slot it will overwrite), so R_{i-1} overlaps V_i.  `stream_recompute` first
+ * waits for everything already enqueued on `stream_grad` and is joined back
+ * into `stream_grad` before the call returns.  The two streams must differ and
+ * must have the same (default) priority. */
+int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params,
+                                const float* Y1, const float* Y2,
+                                const float* dY1, const float* dY2,
+                                float* dX1, float* dX2,
+                                float* X1_out, float* X2_out, float* dparams,
+                                void* workspace, int64_t workspace_bytes,
+                                void* stream_grad, void* stream_recompute);
+
+/* Measurement aid for the hidden-recompute fraction: runs only one of the two
+ * chains of the backward pass on `stream`.  chain = 0: the recomputation chain
+ * R_N..R_1 alone (writes X1_out/X2_out if given).  chain = 1: the gradient
+ * chain V_N..V_1 alone, reading whatever the two activation slots and the
+ * residual ring currently hold (run a full backward first so they hold finite
+ * values); its outputs are meaningful as timings only. */
+int rev_stack_backward_chain(const rev_cfg* cfg, const void* params,
+                             const float* Y1, const float* Y2,
+                             const float* dY1, const float* dY2,
+                             float* dX1, float* dX2,
+                             float* X1_out, float* X2_out, float* dparams,
+                             void* workspace, int64_t workspace_bytes,
+                             void* stream, int32_t chain);
+
+/* Per-kernel-family timing.  Between rev_profile_begin() and rev_profile_end()
+ * every kernel launch made by the calling process is bracketed by a pair of
+ * HIP events on the stream it is launched on.  rev_profile_end() synchronises
+ * the device, folds the elapsed times into per-family totals and stops
+ * recording.  rev_profile_get() returns, for family `kind` (0 <=
+ * kind < rev_profile_kinds()), its name, total milliseconds, launch count and
+ * the algorithmic work of those launches (flops for matrix-core families, HBM
+ * bytes for the others; see rev_profile_is_flops).  Totals accumulate until
+ * rev_profile_begin() is called again.  Not thread safe. */
+int         rev_profile_begin(void);
+int         rev_profile_end(void);
+int         rev_profile_kinds(void);
+const char* rev_profile_name(int kind);
+int         rev_profile_is_flops(int kind);
+int         rev_profile_get(int kind, double* total_ms, int64_t* launches, double* work);
+
+/* Text of the last error reported on this thread ("" if none). */
+const char* rev_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REV_STACK_H */

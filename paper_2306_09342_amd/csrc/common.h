@@ -1,0 +1,157 @@
+// Internal declarations shared by the translation units of librevstack.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <string>
+
+#include "rev_stack.h"
+
+namespace rev {
+
+typedef __hip_bfloat16 bf16;
+
+// ---- error plumbing -------------------------------------------------------
+void set_error(const std::string& msg);
+int  hip_fail(hipError_t e, const char* what, const char* file, int line);
+
+#define REV_HIP(expr)                                                        \
+    do {                                                                     \
+        hipError_t _e = (expr);                                              \
+        if (_e != hipSuccess) return ::rev::hip_fail(_e, #expr, __FILE__, __LINE__); \
+    } while (0)
+
+// ---- kernel families for the per-family timing ------------------------------
+enum Kind {
+    K_GEMM_NT = 0,   // activation x weight^T contractions (forward/recompute and dgrad)
+    K_GEMM_WGRAD,    // weight-gradient contractions (long reduction over tokens)
+    K_ATTN_FWD,
+    K_ATTN_BWD,
+    K_LN_FWD,
+    K_LN_BWD,
+    K_COLSUM,        // bias gradients (column sums), first stage
+    K_REDUCE,        // fixed-order second stage of column sums / split reductions
+    K_CONVERT,       // dtype conversion and weight transposes
+    K_COUNT
+};
+
+// Brackets a launch with events when profiling is on; otherwise nothing.
+struct ProfScope {
+    ProfScope(Kind k, hipStream_t s, double work);
+    ~ProfScope();
+    Kind kind; hipStream_t stream; void* rec;
+};
+bool profiling();
+
+// ---- small device helpers ------------------------------------------------------
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(bf16 v) { return __bfloat162float(v); }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f<bf16>(float v) { return __float2bfloat16(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// exact GELU and its derivative (erf form)
+__device__ __forceinline__ float gelu_f(float x) {
+    return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
+}
+__device__ __forceinline__ float gelu_grad_f(float x) {
+    float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+    float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
+    return cdf + x * pdf;
+}
+
+// ---- epilogue description shared by the GEMM launchers ----------------------------
+enum EpiKind {
+    EPI_BIAS = 0,      // out = acc + bias[n]                               (out: act type)
+    EPI_BIAS_GELU,     // h = acc + bias[n]; out = h; out2 = gelu(h)        (act type)
+    EPI_RESIDUAL,      // outf = res[m,n] + sign * (acc + bias[n])          (float32)
+    EPI_GELU_BWD,      // out = acc * gelu'(aux[m,n])                       (act type)
+    EPI_PLAIN,         // out = acc                                         (act type)
+    EPI_PLAIN_F32      // outf = acc                                        (float32)
+};
+
+struct Epi {
+    int kind;
+    void* out;          // act-typed output  [M, ldo]
+    void* out2;         // second act-typed output (gelu)
+    float* outf;        // float32 output
+    const void* bias;   // parameter-typed [N]
+    const float* res;   // float32 [M, ldo]
+    const void* aux;    // act-typed [M, ldo] (pre-activation for GELU backward)
+    float sign;
+    int64_t ldo;
+};
+
+// C[M,N] (+epilogue) = A[M,K] * B[N,K]^T.  A, B row-major with leading dims lda, ldb.
+// fp32 flavour: A, B float.  bf16 flavour: A, B bf16.
+int gemm_nt_f32(hipStream_t s, const float* A, int64_t lda, const float* B, int64_t ldb,
+                int M, int N, int K, const Epi& epi);
+int gemm_nt_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                 int M, int N, int K, const Epi& epi);
+// C[M,N] = A[M,K] * B[K,N]  (B row-major [K, ldb]); fp32 mode's dgrad.
+int gemm_nn_f32(hipStream_t s, const float* A, int64_t lda, const float* B, int64_t ldb,
+                int M, int N, int K, const Epi& epi);
+// dW[N,K] (float32, ld = K) = G[M,N]^T * A[M,K]  -- reduction over the M tokens.
+// `partial` is scratch for the fixed-order split of the reduction (may be unused).
+int gemm_wgrad_f32(hipStream_t s, const float* G, int64_t ldg, const float* A, int64_t lda,
+                   int M, int N, int K, float* dW, float* partial, int64_t partial_elems);
+int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
+                    int M, int N, int K, float* dW, float* partial, int64_t partial_elems);
+
+// plain vector-ALU flavours (also the fall-back for shapes the matrix-core kernels do not take)
+int gemm_nt_bf16_simple(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                        int M, int N, int K, const Epi& epi);
+int gemm_wgrad_bf16_simple(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
+                           int M, int N, int K, float* dW);
+template <typename T>
+int attention_forward_simple(hipStream_t s, const T* qkv, T* o, float* lse, int B, int T_, int H, int dh);
+template <typename T>
+int attention_backward_simple(hipStream_t s, const T* qkv, const T* o, const T* dout, const float* lse,
+                              T* dqkv, float* delta, int B, int T_, int H, int dh);
+
+// ---- memory-bound kernels ---------------------------------------------------------
+// y = LN(x; g, b), stats[2*row] = mean, stats[2*row+1] = rstd
+template <typename TA, typename TP>
+int ln_forward(hipStream_t s, const float* x, const TP* g, const TP* b, float eps,
+               TA* y, float* stats, int M, int D);
+// out = r + LNbwd(dn; x, stats, g);  outb (nullable) = act-typed copy of out;
+// dg, db = column reductions (float32 [D]) via `partial` (>= ln_bwd_partial_elems floats)
+template <typename TA, typename TP>
+int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats, const TP* g,
+                const float* r, float* out, TA* outb, float* dg, float* db,
+                float* partial, int M, int D);
+int64_t ln_bwd_partial_elems(int M, int D);
+
+// out[n] = sum_m in[m, n]   (float32 out, fixed summation order)
+template <typename T>
+int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, float* partial);
+int64_t colsum_partial_elems(int M, int N);
+
+// out[i] = sum_p partial[p * stride + i], p ascending
+int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out);
+
+int convert_f32_to_bf16(hipStream_t s, const float* in, bf16* out, int64_t n);
+int copy_f32(hipStream_t s, const float* in, float* out, int64_t n);
+// out[c, r] = in[r, c]  (in: [R, C] row-major)
+int transpose_bf16(hipStream_t s, const bf16* in, bf16* out, int R, int C);
+
+// ---- attention ----------------------------------------------------------------------
+// qkv [B*T, 3D] (q|k|v, head-major inside each), o [B*T, D], lse [B, H, T]
+template <typename TA>
+int attention_forward(hipStream_t s, const TA* qkv, TA* o, float* lse, int B, int T, int H, int dh);
+template <typename TA>
+int attention_backward(hipStream_t s, const TA* qkv, const TA* o, const TA* dout, const float* lse,
+                       TA* dqkv, float* delta, int B, int T, int H, int dh);
+
+}  // namespace rev

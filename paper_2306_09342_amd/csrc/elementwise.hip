@@ -1,0 +1,360 @@
+// Memory-bound kernels: LayerNorm forward / backward, column sums, fixed-order
+// reductions, dtype conversion, transposes.  One wavefront (64 lanes) owns one
+// row at a time and keeps it in registers; row statistics are wavefront
+// reductions; column statistics (d gamma, d beta, bias gradients) are summed in
+// a fixed order so that results do not depend on scheduling.
+#include "common.h"
+
+namespace rev {
+
+// ---- 4-element vector access for float and bf16 -------------------------------
+struct f4 { float x, y, z, w; };
+
+__device__ __forceinline__ f4 load4(const float* p) {
+    float4 v = *reinterpret_cast<const float4*>(p);
+    return {v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ f4 load4(const bf16* p) {
+    uint2 u = *reinterpret_cast<const uint2*>(p);
+    f4 r;
+    r.x = __uint_as_float(u.x << 16);
+    r.y = __uint_as_float(u.x & 0xFFFF0000u);
+    r.z = __uint_as_float(u.y << 16);
+    r.w = __uint_as_float(u.y & 0xFFFF0000u);
+    return r;
+}
+__device__ __forceinline__ void store4(float* p, f4 v) {
+    *reinterpret_cast<float4*>(p) = make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    bf16 a = __float2bfloat16(lo), b = __float2bfloat16(hi);
+    uint16_t ua = *reinterpret_cast<uint16_t*>(&a), ub = *reinterpret_cast<uint16_t*>(&b);
+    return (uint32_t)ua | ((uint32_t)ub << 16);
+}
+__device__ __forceinline__ void store4(bf16* p, f4 v) {
+    uint2 u;
+    u.x = pack_bf16x2(v.x, v.y);
+    u.y = pack_bf16x2(v.z, v.w);
+    *reinterpret_cast<uint2*>(p) = u;
+}
+
+// ---- LayerNorm forward -----------------------------------------------------------
+// Lane l of the row's wavefront holds 4-element chunks l, l+64, ... (MAXJ of them).
+template <typename TA, typename TP, int MAXJ>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const float* __restrict__ x, const TP* __restrict__ g,
+                                                     const TP* __restrict__ b, float eps,
+                                                     TA* __restrict__ y, float* __restrict__ stats,
+                                                     int M, int D) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= M) return;
+    const int nch = D >> 2;
+    const float* xr = x + (int64_t)row * D;
+    f4 v[MAXJ];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        int c = lane + 64 * j;
+        if (c < nch) {
+            v[j] = load4(xr + 4 * c);
+            s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+        }
+    }
+    const float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        int c = lane + 64 * j;
+        if (c < nch) {
+            float a0 = v[j].x - mean, a1 = v[j].y - mean, a2 = v[j].z - mean, a3 = v[j].w - mean;
+            q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+        }
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)D + eps);
+    TA* yr = y + (int64_t)row * D;
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        int c = lane + 64 * j;
+        if (c < nch) {
+            f4 gg = load4(g + 4 * c), bb = load4(b + 4 * c), o;
+            o.x = (v[j].x - mean) * rstd * gg.x + bb.x;
+            o.y = (v[j].y - mean) * rstd * gg.y + bb.y;
+            o.z = (v[j].z - mean) * rstd * gg.z + bb.z;
+            o.w = (v[j].w - mean) * rstd * gg.w + bb.w;
+            store4(yr + 4 * c, o);
+        }
+    }
+    if (lane == 0) {
+        stats[2 * (int64_t)row] = mean;
+        stats[2 * (int64_t)row + 1] = rstd;
+    }
+}
+
+static int pick_maxj(int D) {
+    int nch = D / 4, need = (nch + 63) / 64;
+    int j = 2;
+    while (j < need) j *= 2;
+    return j;   // 2,4,8,16,32  (D <= 8192)
+}
+
+template <typename TA, typename TP>
+int ln_forward(hipStream_t s, const float* x, const TP* g, const TP* b, float eps,
+               TA* y, float* stats, int M, int D) {
+    ProfScope ps(K_LN_FWD, s, (double)M * D * (4 + sizeof(TA)));
+    dim3 grid((M + 3) / 4), block(256);
+    switch (pick_maxj(D)) {
+#define CASE(J) case J: hipLaunchKernelGGL((ln_fwd_kernel<TA, TP, J>), grid, block, 0, s, x, g, b, eps, y, stats, M, D); break;
+        CASE(2) CASE(4) CASE(8) CASE(16) CASE(32)
+#undef CASE
+        default: set_error("ln_forward: d_model too large"); return REV_EINVAL;
+    }
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+template int ln_forward<float, float>(hipStream_t, const float*, const float*, const float*, float, float*, float*, int, int);
+template int ln_forward<bf16, bf16>(hipStream_t, const float*, const bf16*, const bf16*, float, bf16*, float*, int, int);
+
+// ---- LayerNorm backward + residual-gradient add -----------------------------------------
+// out = r + rstd * (dxh - mean(dxh) - xhat * mean(dxh * xhat)),  dxh = dn * g.
+// Each block walks LNB_ROWS consecutive rows (4 wavefronts, one row each at a
+// time); per-lane column accumulators for d gamma / d beta are folded across the
+// 4 wavefronts in LDS in wavefront order and written as one partial row per block.
+constexpr int LNB_ROWS = 32;
+
+template <typename TA, typename TP, int MAXJ>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, const float* __restrict__ x,
+                                                     const float* __restrict__ stats, const TP* __restrict__ g,
+                                                     const float* __restrict__ r, float* __restrict__ out,
+                                                     TA* __restrict__ outb, float* __restrict__ partial,
+                                                     int M, int D) {
+    extern __shared__ float lds[];   // [2 * D]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nch = D >> 2;
+    f4 ag[MAXJ], ab[MAXJ], gg[MAXJ];
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) {
+        ag[j] = {0.f, 0.f, 0.f, 0.f};
+        ab[j] = {0.f, 0.f, 0.f, 0.f};
+        int c = lane + 64 * j;
+        gg[j] = (c < nch) ? load4(g + 4 * c) : f4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int row0 = blockIdx.x * LNB_ROWS;
+    const int row1 = min(M, row0 + LNB_ROWS);
+    for (int row = row0 + wave; row < row1; row += 4) {
+        const float mean = stats[2 * (int64_t)row], rstd = stats[2 * (int64_t)row + 1];
+        const int64_t base = (int64_t)row * D;
+        f4 xh[MAXJ], dh[MAXJ];
+        float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            int c = lane + 64 * j;
+            if (c < nch) {
+                f4 xv = load4(x + base + 4 * c), d = load4(dn + base + 4 * c);
+                xh[j] = {(xv.x - mean) * rstd, (xv.y - mean) * rstd, (xv.z - mean) * rstd, (xv.w - mean) * rstd};
+                ab[j].x += d.x; ab[j].y += d.y; ab[j].z += d.z; ab[j].w += d.w;
+                ag[j].x += d.x * xh[j].x; ag[j].y += d.y * xh[j].y;
+                ag[j].z += d.z * xh[j].z; ag[j].w += d.w * xh[j].w;
+                dh[j] = {d.x * gg[j].x, d.y * gg[j].y, d.z * gg[j].z, d.w * gg[j].w};
+                c1 += (dh[j].x + dh[j].y) + (dh[j].z + dh[j].w);
+                c2 += (dh[j].x * xh[j].x + dh[j].y * xh[j].y) + (dh[j].z * xh[j].z + dh[j].w * xh[j].w);
+            }
+        }
+        c1 = wave_sum(c1) / (float)D;
+        c2 = wave_sum(c2) / (float)D;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            int c = lane + 64 * j;
+            if (c < nch) {
+                f4 rv = load4(r + base + 4 * c), o;
+                o.x = rv.x + rstd * (dh[j].x - c1 - xh[j].x * c2);
+                o.y = rv.y + rstd * (dh[j].y - c1 - xh[j].y * c2);
+                o.z = rv.z + rstd * (dh[j].z - c1 - xh[j].z * c2);
+                o.w = rv.w + rstd * (dh[j].w - c1 - xh[j].w * c2);
+                store4(out + base + 4 * c, o);
+                if (outb) store4(outb + base + 4 * c, o);
+            }
+        }
+    }
+    // fold the 4 wavefronts' column accumulators in wavefront order
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int j = 0; j < MAXJ; ++j) {
+                int c = lane + 64 * j;
+                if (c < nch) {
+                    float* pg = lds + 4 * c;
+                    float* pb = lds + D + 4 * c;
+                    if (w == 0) {
+                        pg[0] = ag[j].x; pg[1] = ag[j].y; pg[2] = ag[j].z; pg[3] = ag[j].w;
+                        pb[0] = ab[j].x; pb[1] = ab[j].y; pb[2] = ab[j].z; pb[3] = ab[j].w;
+                    } else {
+                        pg[0] += ag[j].x; pg[1] += ag[j].y; pg[2] += ag[j].z; pg[3] += ag[j].w;
+                        pb[0] += ab[j].x; pb[1] += ab[j].y; pb[2] += ab[j].z; pb[3] += ab[j].w;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    float* prow = partial + (int64_t)blockIdx.x * 2 * D;
+    for (int i = threadIdx.x; i < 2 * D; i += 256) prow[i] = lds[i];
+}
+
+// out[i] = sum over p (ascending) of partial[p * stride + i]; 4 elements per thread.
+__global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ partial, int P,
+                                                          int64_t stride, int64_t n4, float* __restrict__ out) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = 0; p < P; ++p) {
+        float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * stride + 4 * i);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *reinterpret_cast<float4*>(out + 4 * i) = acc;
+}
+
+int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out) {
+    if (n % 4 != 0) { set_error("reduce_rows: length must be a multiple of 4"); return REV_EINVAL; }
+    ProfScope ps(K_REDUCE, s, (double)(P + 1) * n * 4);
+    int64_t n4 = n / 4;
+    dim3 grid((unsigned)((n4 + 255) / 256)), block(256);
+    hipLaunchKernelGGL(reduce_rows_kernel, grid, block, 0, s, partial, P, stride, n4, out);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+int64_t ln_bwd_partial_elems(int M, int D) {
+    return (int64_t)((M + LNB_ROWS - 1) / LNB_ROWS) * 2 * D;
+}
+
+template <typename TA, typename TP>
+int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats, const TP* g,
+                const float* r, float* out, TA* outb, float* dg, float* db,
+                float* partial, int M, int D) {
+    const int nblk = (M + LNB_ROWS - 1) / LNB_ROWS;
+    {
+        ProfScope ps(K_LN_BWD, s, (double)M * D * (sizeof(TA) + 4 + 4 + 4 + (outb ? sizeof(TA) : 0)));
+        dim3 grid(nblk), block(256);
+        size_t shmem = (size_t)2 * D * sizeof(float);
+        switch (pick_maxj(D)) {
+#define CASE(J) case J: hipLaunchKernelGGL((ln_bwd_kernel<TA, TP, J>), grid, block, shmem, s, dn, x, stats, g, r, out, outb, partial, M, D); break;
+            CASE(2) CASE(4) CASE(8) CASE(16) CASE(32)
+#undef CASE
+            default: set_error("ln_backward: d_model too large"); return REV_EINVAL;
+        }
+        REV_HIP(hipGetLastError());
+    }
+    // partial rows are [dgamma(D) | dbeta(D)]; dg and db are separate outputs
+    int rc = reduce_rows(s, partial, nblk, 2 * (int64_t)D, D, dg);
+    if (rc) return rc;
+    return reduce_rows(s, partial + D, nblk, 2 * (int64_t)D, D, db);
+}
+template int ln_backward<float, float>(hipStream_t, const float*, const float*, const float*, const float*, const float*, float*, float*, float*, float*, float*, int, int);
+template int ln_backward<bf16, bf16>(hipStream_t, const bf16*, const float*, const float*, const bf16*, const float*, float*, bf16*, float*, float*, float*, int, int);
+
+// ---- column sums (bias gradients) --------------------------------------------------------
+// grid (column tiles of 256, row chunks); each wavefront sums a quarter of the
+// block's rows for its 256 columns, the 4 wavefronts are folded in order.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ in, int64_t ld, int M, int N,
+                                                     int rows_per_block, float* __restrict__ partial) {
+    __shared__ float lds[4][256];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int col = blockIdx.x * 256 + lane * 4;
+    const int row0 = blockIdx.y * rows_per_block;
+    const int row1 = min(M, row0 + rows_per_block);
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (col < N) {
+        for (int row = row0 + wave; row < row1; row += 4) {
+            f4 v = load4(in + (int64_t)row * ld + col);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    }
+    lds[wave][lane * 4 + 0] = acc.x; lds[wave][lane * 4 + 1] = acc.y;
+    lds[wave][lane * 4 + 2] = acc.z; lds[wave][lane * 4 + 3] = acc.w;
+    __syncthreads();
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < N) {
+        float v = ((lds[0][threadIdx.x] + lds[1][threadIdx.x]) + lds[2][threadIdx.x]) + lds[3][threadIdx.x];
+        partial[(int64_t)blockIdx.y * N + c] = v;
+    }
+}
+
+static int colsum_chunks(int M, int N) {
+    int tiles = (N + 255) / 256;
+    int P = (2048 + tiles - 1) / tiles;
+    int maxP = (M + 15) / 16;
+    if (P > maxP) P = maxP;
+    if (P < 1) P = 1;
+    return P;
+}
+int64_t colsum_partial_elems(int M, int N) { return (int64_t)colsum_chunks(M, N) * N; }
+
+template <typename T>
+int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, float* partial) {
+    int P = colsum_chunks(M, N);
+    int rpb = (M + P - 1) / P;
+    P = (M + rpb - 1) / rpb;
+    {
+        ProfScope ps(K_COLSUM, s, (double)M * N * sizeof(T));
+        dim3 grid((N + 255) / 256, P), block(256);
+        hipLaunchKernelGGL((colsum_kernel<T>), grid, block, 0, s, in, ld, M, N, rpb, partial);
+        REV_HIP(hipGetLastError());
+    }
+    return reduce_rows(s, partial, P, N, N, out);
+}
+template int colsum<float>(hipStream_t, const float*, int64_t, int, int, float*, float*);
+template int colsum<bf16>(hipStream_t, const bf16*, int64_t, int, int, float*, float*);
+
+// ---- conversion, copy, transpose ------------------------------------------------------------
+__global__ __launch_bounds__(256) void cvt_kernel(const float* __restrict__ in, bf16* __restrict__ out, int64_t n4) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) store4(out + 4 * i, load4(in + 4 * i));
+}
+int convert_f32_to_bf16(hipStream_t s, const float* in, bf16* out, int64_t n) {
+    if (n % 4 != 0) { set_error("convert: length must be a multiple of 4"); return REV_EINVAL; }
+    ProfScope ps(K_CONVERT, s, (double)n * 6);
+    int64_t n4 = n / 4;
+    hipLaunchKernelGGL(cvt_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, in, out, n4);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const float* __restrict__ in, float* __restrict__ out, int64_t n4) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) store4(out + 4 * i, load4(in + 4 * i));
+}
+int copy_f32(hipStream_t s, const float* in, float* out, int64_t n) {
+    if (n % 4 != 0) { set_error("copy: length must be a multiple of 4"); return REV_EINVAL; }
+    ProfScope ps(K_CONVERT, s, (double)n * 8);
+    int64_t n4 = n / 4;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, in, out, n4);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+__global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
+                                                        int R, int C) {
+    __shared__ uint16_t tile[64][66];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        int r = r0 + i, c = c0 + tx;
+        if (r < R && c < C) tile[i][tx] = in[(int64_t)r * C + c];
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        int c = c0 + i, r = r0 + tx;
+        if (r < R && c < C) out[(int64_t)c * R + r] = tile[tx][i];
+    }
+}
+int transpose_bf16(hipStream_t s, const bf16* in, bf16* out, int R, int C) {
+    ProfScope ps(K_CONVERT, s, (double)R * C * 4);
+    dim3 grid((C + 63) / 64, (R + 63) / 64), block(256);
+    hipLaunchKernelGGL(transpose_kernel, grid, block, 0, s, reinterpret_cast<const uint16_t*>(in),
+                       reinterpret_cast<uint16_t*>(out), R, C);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+}  // namespace rev

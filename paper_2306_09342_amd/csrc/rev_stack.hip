@@ -1,0 +1,575 @@
+// Host side of librevstack: argument checks, workspace layout, the per-block
+// recompute (R_i) and gradient (V_i) kernel sequences, and the two schedules
+// of the paper's Sec. 3.2 (Reprop: one stream) and Sec. 3.3 (PaReprop: the
+// recomputation chain on a second stream, ordered against the gradient chain
+// by events and a double-buffered activation slot).
+#include "common.h"
+
+#include <mutex>
+#include <vector>
+
+namespace rev {
+
+// ---------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------
+static thread_local std::string g_err;
+void set_error(const std::string& msg) { g_err = msg; }
+int hip_fail(hipError_t e, const char* what, const char* file, int line) {
+    g_err = std::string(hipGetErrorString(e)) + " in " + what + " (" + file + ":" + std::to_string(line) + ")";
+    return REV_EHIP;
+}
+
+// ---------------------------------------------------------------------------------
+// per-family timing
+// ---------------------------------------------------------------------------------
+struct ProfRec { Kind kind; hipEvent_t e0, e1; };
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof_recs;
+static double g_prof_ms[K_COUNT];
+static int64_t g_prof_n[K_COUNT];
+static double g_prof_work[K_COUNT];
+static const char* g_kind_names[K_COUNT] = {"gemm_nt", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd",
+                                            "ln_bwd", "colsum", "reduce", "convert"};
+static const int g_kind_flops[K_COUNT] = {1, 1, 1, 1, 0, 0, 0, 0, 0};
+
+bool profiling() { return g_prof_on; }
+
+ProfScope::ProfScope(Kind k, hipStream_t s, double work) : kind(k), stream(s), rec(nullptr) {
+    if (!g_prof_on) return;
+    ProfRec r;
+    r.kind = k;
+    if (hipEventCreate(&r.e0) != hipSuccess) return;
+    if (hipEventCreate(&r.e1) != hipSuccess) { (void)hipEventDestroy(r.e0); return; }
+    (void)hipEventRecord(r.e0, s);
+    g_prof_recs.push_back(r);
+    g_prof_work[k] += work;
+    rec = (void*)(uintptr_t)g_prof_recs.size();   // index + 1
+}
+ProfScope::~ProfScope() {
+    if (rec) (void)hipEventRecord(g_prof_recs[(uintptr_t)rec - 1].e1, stream);
+}
+
+// ---------------------------------------------------------------------------------
+// configuration and packed-parameter layout
+// ---------------------------------------------------------------------------------
+enum { T_LN1G = 0, T_LN1B, T_WQKV, T_BQKV, T_WPROJ, T_BPROJ, T_LN2G, T_LN2B, T_WFC1, T_BFC1, T_WFC2, T_BFC2, T_COUNT };
+
+static int64_t tensor_count(const rev_cfg& c, int t) {
+    const int64_t D = c.d_model, Dm = c.d_mlp;
+    switch (t) {
+        case T_WQKV: return 3 * D * D;
+        case T_BQKV: return 3 * D;
+        case T_WPROJ: return D * D;
+        case T_WFC1: case T_WFC2: return D * Dm;
+        case T_BFC1: return Dm;
+        default: return D;
+    }
+}
+static int64_t tensor_offset(const rev_cfg& c, int t) {
+    int64_t off = 0;
+    for (int i = 0; i < t; ++i) off += tensor_count(c, i);
+    return off;
+}
+static int64_t block_params(const rev_cfg& c) { return tensor_offset(c, T_COUNT); }
+
+static int check_cfg(const rev_cfg* c) {
+    if (!c) { set_error("cfg is null"); return REV_EINVAL; }
+    if (c->n_blocks <= 0 || c->d_model <= 0 || c->n_heads <= 0 || c->d_mlp <= 0 || c->seq_len <= 0 || c->batch <= 0) {
+        set_error("cfg: every size must be positive"); return REV_EINVAL;
+    }
+    if (c->mode != REV_MODE_FP32 && c->mode != REV_MODE_BF16) { set_error("cfg: unknown mode"); return REV_EINVAL; }
+    if (c->d_model % c->n_heads != 0) { set_error("cfg: d_model must be divisible by n_heads"); return REV_EINVAL; }
+    const int dh = c->d_model / c->n_heads;
+    if (c->d_model % 8 != 0 || c->d_mlp % 8 != 0 || dh % 8 != 0) {
+        set_error("cfg: d_model, d_mlp and head_dim must be multiples of 8"); return REV_EINVAL;
+    }
+    if (dh > 128) { set_error("cfg: head_dim must be <= 128"); return REV_EINVAL; }
+    if (c->d_model > 8192 || c->d_mlp > 32768) { set_error("cfg: d_model <= 8192 and d_mlp <= 32768"); return REV_EINVAL; }
+    if ((int64_t)c->batch * c->seq_len >= (1 << 24)) { set_error("cfg: batch*seq_len must be < 2^24"); return REV_EINVAL; }
+    if (!(c->ln_eps >= 0.f)) { set_error("cfg: ln_eps must be >= 0"); return REV_EINVAL; }
+    return REV_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// workspace layout (byte offsets, every region 256-byte aligned)
+// ---------------------------------------------------------------------------------
+int64_t wgrad_partial_elems(int M, int N, int K);   // gemm_mfma.hip
+
+struct Layout {
+    int64_t slot[2];
+    int64_t s_n2, s_h, s_a, s_n1, s_qkv, s_o, s_lse, s_st1, s_st2;   // relative to a slot
+    int64_t ring[3][2];
+    int64_t cot[2][2];     // float32 cotangent levels
+    int64_t cot2b[2];      // act-typed copy of the stream-2 cotangent (bf16 mode)
+    int64_t gy1b;          // act-typed copy of gY1 (bf16 mode)
+    int64_t dh, dn, dO, dqkv, delta;
+    int64_t part_ln, part_col, part_wg;
+    int64_t wT;            // transposed weights (bf16 mode): per block WqkvT | WprojT | W1T | W2T
+    int64_t total;
+    int64_t part_wg_elems, wT_block;
+};
+
+static Layout make_layout(const rev_cfg& c) {
+    Layout L = {};
+    const int64_t M = (int64_t)c.batch * c.seq_len, D = c.d_model, Dm = c.d_mlp;
+    const int64_t es = (c.mode == REV_MODE_BF16) ? 2 : 4;
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) { int64_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+    // one activation slot
+    {
+        int64_t base = off;
+        L.s_n2 = take(M * D * es) - base;
+        L.s_h = take(M * Dm * es) - base;
+        L.s_a = take(M * Dm * es) - base;
+        L.s_n1 = take(M * D * es) - base;
+        L.s_qkv = take(M * 3 * D * es) - base;
+        L.s_o = take(M * D * es) - base;
+        L.s_lse = take((int64_t)c.batch * c.n_heads * c.seq_len * 4) - base;
+        L.s_st1 = take(M * 2 * 4) - base;
+        L.s_st2 = take(M * 2 * 4) - base;
+        int64_t slot_bytes = off - base;
+        L.slot[0] = base;
+        L.slot[1] = take(slot_bytes);
+    }
+    for (int r = 0; r < 3; ++r)
+        for (int s = 0; s < 2; ++s) L.ring[r][s] = take(M * D * 4);
+    for (int r = 0; r < 2; ++r)
+        for (int s = 0; s < 2; ++s) L.cot[r][s] = take(M * D * 4);
+    if (c.mode == REV_MODE_BF16) {
+        L.cot2b[0] = take(M * D * es);
+        L.cot2b[1] = take(M * D * es);
+        L.gy1b = take(M * D * es);
+    }
+    L.dh = take(M * Dm * es);
+    L.dn = take(M * D * es);
+    L.dO = take(M * D * es);
+    L.dqkv = take(M * 3 * D * es);
+    L.delta = take((int64_t)c.batch * c.n_heads * c.seq_len * 4);
+    L.part_ln = take(ln_bwd_partial_elems((int)M, (int)D) * 4);
+    {
+        int64_t e = colsum_partial_elems((int)M, (int)D);
+        int64_t e2 = colsum_partial_elems((int)M, (int)Dm);
+        int64_t e3 = colsum_partial_elems((int)M, (int)(3 * D));
+        if (e2 > e) e = e2;
+        if (e3 > e) e = e3;
+        L.part_col = take(e * 4);
+    }
+    if (c.mode == REV_MODE_BF16) {
+        int64_t e = wgrad_partial_elems((int)M, (int)D, (int)Dm);
+        int64_t e2 = wgrad_partial_elems((int)M, (int)Dm, (int)D);
+        int64_t e3 = wgrad_partial_elems((int)M, (int)D, (int)D);
+        int64_t e4 = wgrad_partial_elems((int)M, (int)(3 * D), (int)D);
+        if (e2 > e) e = e2;
+        if (e3 > e) e = e3;
+        if (e4 > e) e = e4;
+        L.part_wg_elems = e;
+        L.part_wg = take(e * 4);
+        L.wT_block = 4 * D * D + 2 * D * Dm;
+        L.wT = take(L.wT_block * c.n_blocks * es);
+    }
+    L.total = off;
+    return L;
+}
+
+// ---------------------------------------------------------------------------------
+// event pool (the only state kept between calls)
+// ---------------------------------------------------------------------------------
+static std::mutex g_ev_mu;
+static std::vector<hipEvent_t> g_events;
+static int get_events(int n, std::vector<hipEvent_t>& out) {
+    std::lock_guard<std::mutex> lk(g_ev_mu);
+    while ((int)g_events.size() < n) {
+        hipEvent_t e;
+        REV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        g_events.push_back(e);
+    }
+    out.assign(g_events.begin(), g_events.begin() + n);
+    return REV_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// the per-block kernel sequences
+// ---------------------------------------------------------------------------------
+#define RC(expr) do { int _rc = (expr); if (_rc != REV_OK) return _rc; } while (0)
+
+template <typename T> struct Ops;
+template <> struct Ops<float> {
+    static int nt(hipStream_t s, const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, const Epi& e) {
+        return gemm_nt_f32(s, A, lda, B, ldb, M, N, K, e);
+    }
+    static int wgrad(hipStream_t s, const float* G, int64_t ldg, const float* A, int64_t lda, int M, int N, int K,
+                     float* dW, float* part, int64_t pe) {
+        return gemm_wgrad_f32(s, G, ldg, A, lda, M, N, K, dW, part, pe);
+    }
+};
+template <> struct Ops<bf16> {
+    static int nt(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K, const Epi& e) {
+        return gemm_nt_bf16(s, A, lda, B, ldb, M, N, K, e);
+    }
+    static int wgrad(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,
+                     float* dW, float* part, int64_t pe) {
+        return gemm_wgrad_bf16(s, G, ldg, A, lda, M, N, K, dW, part, pe);
+    }
+};
+
+template <typename T>
+struct Runner {
+    static constexpr bool kBf16 = sizeof(T) == 2;
+    rev_cfg c;
+    Layout L;
+    char* ws;
+    const T* params;
+    float* dparams;
+    int M, D, Dm, H, dh, B, Tn;
+
+    Runner(const rev_cfg& cfg, const void* p, float* dp, void* w)
+        : c(cfg), L(make_layout(cfg)), ws((char*)w), params((const T*)p), dparams(dp) {
+        M = c.batch * c.seq_len; D = c.d_model; Dm = c.d_mlp; H = c.n_heads; dh = D / H; B = c.batch; Tn = c.seq_len;
+    }
+    template <typename U> U* at(int64_t off) const { return reinterpret_cast<U*>(ws + off); }
+    const T* P(int blk, int t) const { return params + (int64_t)blk * block_params(c) + tensor_offset(c, t); }
+    float* G(int blk, int t) const { return dparams + (int64_t)blk * block_params(c) + tensor_offset(c, t); }
+    // transposed weight copies (bf16 mode): [in, out] row-major
+    const T* WT(int blk, int which) const {
+        int64_t o = (int64_t)blk * L.wT_block;
+        const int64_t DD = (int64_t)D * D;
+        if (which >= 1) o += 3 * DD;                 // after WqkvT
+        if (which >= 2) o += DD;                     // after WprojT
+        if (which >= 3) o += (int64_t)D * Dm;        // after W1T
+        return at<T>(L.wT) + o;
+    }
+
+    struct Slot { T *n2, *h, *a, *n1, *qkv, *o; float *lse, *st1, *st2; };
+    Slot slot(int i) const {
+        int64_t b = L.slot[i & 1];
+        return {at<T>(b + L.s_n2), at<T>(b + L.s_h), at<T>(b + L.s_a), at<T>(b + L.s_n1), at<T>(b + L.s_qkv),
+                at<T>(b + L.s_o), at<float>(b + L.s_lse), at<float>(b + L.s_st1), at<float>(b + L.s_st2)};
+    }
+
+    // F branch pieces up to the projection input: n1, qkv, o, lse from x2
+    int f_pre(hipStream_t s, int blk, const float* x2, const Slot& sl) {
+        RC((ln_forward<T, T>(s, x2, P(blk, T_LN1G), P(blk, T_LN1B), c.ln_eps, sl.n1, sl.st1, M, D)));
+        Epi e = {}; e.kind = EPI_BIAS; e.out = sl.qkv; e.bias = P(blk, T_BQKV); e.ldo = 3 * D;
+        RC(Ops<T>::nt(s, sl.n1, D, P(blk, T_WQKV), D, M, 3 * D, D, e));
+        RC((attention_forward<T>(s, sl.qkv, sl.o, sl.lse, B, Tn, H, dh)));
+        return REV_OK;
+    }
+    // out1 = in1 + sign * (o Wp^T + bp)
+    int f_post(hipStream_t s, int blk, const Slot& sl, const float* in1, float* out1, float sign) {
+        Epi e = {}; e.kind = EPI_RESIDUAL; e.outf = out1; e.res = in1; e.bias = P(blk, T_BPROJ); e.sign = sign; e.ldo = D;
+        return Ops<T>::nt(s, sl.o, D, P(blk, T_WPROJ), D, M, D, D, e);
+    }
+    // out2 = in2 + sign * G(y1)
+    int g_branch(hipStream_t s, int blk, const float* y1, const Slot& sl, const float* in2, float* out2, float sign) {
+        RC((ln_forward<T, T>(s, y1, P(blk, T_LN2G), P(blk, T_LN2B), c.ln_eps, sl.n2, sl.st2, M, D)));
+        Epi e = {}; e.kind = EPI_BIAS_GELU; e.out = sl.h; e.out2 = sl.a; e.bias = P(blk, T_BFC1); e.ldo = Dm;
+        RC(Ops<T>::nt(s, sl.n2, D, P(blk, T_WFC1), D, M, Dm, D, e));
+        Epi r = {}; r.kind = EPI_RESIDUAL; r.outf = out2; r.res = in2; r.bias = P(blk, T_BFC2); r.sign = sign; r.ldo = D;
+        return Ops<T>::nt(s, sl.a, Dm, P(blk, T_WFC2), Dm, M, D, Dm, r);
+    }
+
+    // forward of block blk (0-based): (x1,x2) -> (y1,y2)
+    int forward_block(hipStream_t s, int blk, const float* x1, const float* x2, float* y1, float* y2) {
+        Slot sl = slot(0);
+        RC(f_pre(s, blk, x2, sl));
+        RC(f_post(s, blk, sl, x1, y1, 1.f));
+        return g_branch(s, blk, y1, sl, x2, y2, 1.f);
+    }
+
+    // R_i: (y1,y2) -> (x1,x2) and the slot of block blk
+    int recompute(hipStream_t s, int blk, const float* y1, const float* y2, float* x1, float* x2) {
+        Slot sl = slot(blk);
+        RC(g_branch(s, blk, y1, sl, y2, x2, -1.f));
+        RC(f_pre(s, blk, x2, sl));
+        return f_post(s, blk, sl, y1, x1, -1.f);
+    }
+
+    int transpose_weights(hipStream_t s) {
+        if constexpr (kBf16) {
+            for (int blk = 0; blk < c.n_blocks; ++blk) {
+                RC(transpose_bf16(s, P(blk, T_WQKV), const_cast<T*>(WT(blk, 0)), 3 * D, D));
+                RC(transpose_bf16(s, P(blk, T_WPROJ), const_cast<T*>(WT(blk, 1)), D, D));
+                RC(transpose_bf16(s, P(blk, T_WFC1), const_cast<T*>(WT(blk, 2)), Dm, D));
+                RC(transpose_bf16(s, P(blk, T_WFC2), const_cast<T*>(WT(blk, 3)), D, Dm));
+            }
+        }
+        return REV_OK;
+    }
+
+    // dA[M,Kin] = dC[M,Nout] * W[Nout,Kin]   (which: index of W's transposed copy)
+    int dgrad(hipStream_t s, int blk, int wt, int which, const T* dC, int Nout, int Kin, const Epi& e) {
+        if constexpr (kBf16) {
+            return gemm_nt_bf16(s, dC, Nout, WT(blk, which), Nout, M, Kin, Nout, e);
+        } else {
+            return gemm_nn_f32(s, dC, Nout, P(blk, wt), Kin, M, Kin, Nout, e);
+        }
+    }
+
+    // V_i.  y1: first stream of the block's outputs, x2: second stream of its inputs.
+    // d1, d2: incoming cotangents (float32); d2b: act-typed copy of d2.
+    // o1, o2: outgoing cotangents; o2b: act-typed copy of o2 (nullable).
+    int grad(hipStream_t s, int blk, const float* y1, const float* x2, const float* d1, const float* d2,
+             const T* d2b, float* o1, float* o2, T* o2b) {
+        Slot sl = slot(blk);
+        T* dhb = at<T>(L.dh);
+        T* dn = at<T>(L.dn);
+        T* dO = at<T>(L.dO);
+        T* dqkv = at<T>(L.dqkv);
+        float* pcol = at<float>(L.part_col);
+        float* pln = at<float>(L.part_ln);
+        float* pwg = kBf16 ? at<float>(L.part_wg) : nullptr;
+        T* gy1b = kBf16 ? at<T>(L.gy1b) : reinterpret_cast<T*>(o1);
+
+        // ---- G branch: dh = (dY2 W2) * gelu'(h)
+        Epi e = {}; e.kind = EPI_GELU_BWD; e.out = dhb; e.aux = sl.h; e.ldo = Dm;
+        RC(dgrad(s, blk, T_WFC2, 3, d2b, D, Dm, e));
+        RC(Ops<T>::wgrad(s, d2b, D, sl.a, Dm, M, D, Dm, G(blk, T_WFC2), pwg, L.part_wg_elems));
+        RC(colsum<float>(s, d2, D, M, D, G(blk, T_BFC2), pcol));
+        Epi p = {}; p.kind = EPI_PLAIN; p.out = dn; p.ldo = D;
+        RC(dgrad(s, blk, T_WFC1, 2, dhb, Dm, D, p));
+        RC(Ops<T>::wgrad(s, dhb, Dm, sl.n2, D, M, Dm, D, G(blk, T_WFC1), pwg, L.part_wg_elems));
+        RC(colsum<T>(s, dhb, Dm, M, Dm, G(blk, T_BFC1), pcol));
+        // gY1 = dY1 + LN2bwd(dn)
+        RC((ln_backward<T, T>(s, dn, y1, sl.st2, P(blk, T_LN2G), d1, o1, kBf16 ? gy1b : nullptr,
+                              G(blk, T_LN2G), G(blk, T_LN2B), pln, M, D)));
+        // ---- F branch
+        Epi q = {}; q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
+        RC(dgrad(s, blk, T_WPROJ, 1, gy1b, D, D, q));
+        RC(Ops<T>::wgrad(s, gy1b, D, sl.o, D, M, D, D, G(blk, T_WPROJ), pwg, L.part_wg_elems));
+        RC(colsum<float>(s, o1, D, M, D, G(blk, T_BPROJ), pcol));
+        RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh)));
+        Epi r = {}; r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
+        RC(dgrad(s, blk, T_WQKV, 0, dqkv, 3 * D, D, r));
+        RC(Ops<T>::wgrad(s, dqkv, 3 * D, sl.n1, D, M, 3 * D, D, G(blk, T_WQKV), pwg, L.part_wg_elems));
+        RC(colsum<T>(s, dqkv, 3 * D, M, 3 * D, G(blk, T_BQKV), pcol));
+        // dX2 = dY2 + LN1bwd(dn)
+        RC((ln_backward<T, T>(s, dn, x2, sl.st1, P(blk, T_LN1G), d2, o2, kBf16 ? o2b : nullptr,
+                              G(blk, T_LN1G), G(blk, T_LN1B), pln, M, D)));
+        return REV_OK;
+    }
+
+    // residual level `lvl` (0..N): stream s1/s2 pointers
+    struct Ptrs { const float* in1; const float* in2; float* out1; float* out2; };
+    float* res(int lvl, int st, float* x_out1, float* x_out2) const {
+        if (lvl == 0 && st == 0 && x_out1) return x_out1;
+        if (lvl == 0 && st == 1 && x_out2) return x_out2;
+        return at<float>(L.ring[lvl % 3][st]);
+    }
+
+    // schedule: 0 = Reprop, 1 = PaReprop, 2 = R chain only, 3 = V chain only
+    int backward(int schedule, const float* Y1, const float* Y2, const float* dY1, const float* dY2,
+                 float* dX1, float* dX2, float* X1o, float* X2o, hipStream_t sv, hipStream_t sr) {
+        const int N = c.n_blocks;
+        const bool doR = schedule != 3, doV = schedule != 2;
+        std::vector<hipEvent_t> ev;
+        if (schedule == 1) {
+            RC(get_events(2 * N + 2, ev));
+            REV_HIP(hipEventRecord(ev[2 * N], sv));            // fork
+            REV_HIP(hipStreamWaitEvent(sr, ev[2 * N], 0));
+        } else {
+            sr = sv;
+        }
+        const T* top2b = nullptr;
+        if (doV) {
+            RC(transpose_weights(sv));
+            if constexpr (kBf16) {
+                T* b = at<T>(L.cot2b[N & 1]);
+                RC(convert_f32_to_bf16(sv, dY2, b, (int64_t)M * D));
+                top2b = b;
+            } else {
+                top2b = reinterpret_cast<const T*>(dY2);
+            }
+        }
+        auto run_R = [&](int i) -> int {   // i = N..1 (1-based block index)
+            const float* y1 = (i == N) ? Y1 : res(i, 0, X1o, X2o);
+            const float* y2 = (i == N) ? Y2 : res(i, 1, X1o, X2o);
+            return recompute(sr, i - 1, y1, y2, res(i - 1, 0, X1o, X2o), res(i - 1, 1, X1o, X2o));
+        };
+        auto run_V = [&](int i) -> int {
+            const float* y1 = (i == N) ? Y1 : res(i, 0, X1o, X2o);
+            const float* x2 = res(i - 1, 1, X1o, X2o);
+            const float* d1 = (i == N) ? dY1 : at<float>(L.cot[i & 1][0]);
+            const float* d2 = (i == N) ? dY2 : at<float>(L.cot[i & 1][1]);
+            const T* d2b;
+            if constexpr (kBf16) d2b = (i == N) ? top2b : at<T>(L.cot2b[i & 1]);
+            else d2b = reinterpret_cast<const T*>(d2);
+            float* o1 = (i == 1) ? dX1 : at<float>(L.cot[(i - 1) & 1][0]);
+            float* o2 = (i == 1) ? dX2 : at<float>(L.cot[(i - 1) & 1][1]);
+            T* o2b = nullptr;
+            if constexpr (kBf16) o2b = (i == 1) ? nullptr : at<T>(L.cot2b[(i - 1) & 1]);
+            return grad(sv, i - 1, y1, x2, d1, d2, d2b, o1, o2, o2b);
+        };
+        if (schedule == 1) {
+            // R chain on sr, V chain on sv.  ev[i-1]: R_i done; ev[N+i-1]: V_i done.
+            for (int i = N; i >= 1; --i) {
+                if (i + 2 <= N) REV_HIP(hipStreamWaitEvent(sr, ev[N + (i + 2) - 1], 0));   // slot (and ring level) free
+                RC(run_R(i));
+                REV_HIP(hipEventRecord(ev[i - 1], sr));
+                // enqueue V_{i+1} after R_i so the host feeds both streams in step
+                if (i + 1 <= N) {
+                    REV_HIP(hipStreamWaitEvent(sv, ev[(i + 1) - 1], 0));
+                    RC(run_V(i + 1));
+                    REV_HIP(hipEventRecord(ev[N + (i + 1) - 1], sv));
+                }
+            }
+            REV_HIP(hipStreamWaitEvent(sv, ev[0], 0));
+            RC(run_V(1));
+            // join: sr's last work (R_1) is already ordered before V_1 on sv
+        } else {
+            for (int i = N; i >= 1; --i) {
+                if (doR) RC(run_R(i));
+                if (doV) RC(run_V(i));
+            }
+        }
+        return REV_OK;
+    }
+
+    int forward(const float* X1, const float* X2, float* Y1, float* Y2, hipStream_t s) {
+        const int N = c.n_blocks;
+        for (int i = 1; i <= N; ++i) {
+            const float* x1 = (i == 1) ? X1 : at<float>(L.ring[(i - 1) % 3][0]);
+            const float* x2 = (i == 1) ? X2 : at<float>(L.ring[(i - 1) % 3][1]);
+            float* y1 = (i == N) ? Y1 : at<float>(L.ring[i % 3][0]);
+            float* y2 = (i == N) ? Y2 : at<float>(L.ring[i % 3][1]);
+            RC(forward_block(s, i - 1, x1, x2, y1, y2));
+        }
+        return REV_OK;
+    }
+};
+
+static int check_common(const rev_cfg* cfg, const void* ws, int64_t ws_bytes) {
+    RC(check_cfg(cfg));
+    if (!ws) { set_error("workspace is null"); return REV_EINVAL; }
+    if (((uintptr_t)ws & 255) != 0) { set_error("workspace must be 256-byte aligned"); return REV_EINVAL; }
+    Layout L = make_layout(*cfg);
+    if (ws_bytes < L.total) {
+        set_error("workspace too small: need " + std::to_string(L.total) + " bytes, got " + std::to_string(ws_bytes));
+        return REV_EWORKSPACE;
+    }
+    return REV_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+static int backward_entry(int schedule, const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
+                          const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1o, float* X2o,
+                          float* dparams, void* ws, int64_t ws_bytes, void* sv, void* sr) {
+    RC(check_common(cfg, ws, ws_bytes));
+    if (!params || !Y1 || !Y2 || !dY1 || !dY2 || !dX1 || !dX2 || !dparams) {
+        set_error("a required pointer is null"); return REV_EINVAL;
+    }
+    if (!aligned16(params) || !aligned16(Y1) || !aligned16(Y2) || !aligned16(dY1) || !aligned16(dY2) || !aligned16(dX1) ||
+        !aligned16(dX2) || !aligned16(dparams) || !aligned16(X1o) || !aligned16(X2o)) {
+        set_error("every buffer must be 16-byte aligned"); return REV_EINVAL;
+    }
+    if (schedule == 1 && sv == sr) { set_error("PaReprop needs two different streams"); return REV_EINVAL; }
+    if (cfg->mode == REV_MODE_BF16) {
+        Runner<bf16> r(*cfg, params, dparams, ws);
+        return r.backward(schedule, Y1, Y2, dY1, dY2, dX1, dX2, X1o, X2o, (hipStream_t)sv, (hipStream_t)sr);
+    }
+    Runner<float> r(*cfg, params, dparams, ws);
+    return r.backward(schedule, Y1, Y2, dY1, dY2, dX1, dX2, X1o, X2o, (hipStream_t)sv, (hipStream_t)sr);
+}
+
+}  // namespace rev
+
+using namespace rev;
+
+extern "C" {
+
+int rev_stack_check_cfg(const rev_cfg* cfg) { return check_cfg(cfg); }
+
+int64_t rev_stack_param_count(const rev_cfg* cfg) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    return block_params(*cfg) * cfg->n_blocks;
+}
+
+int64_t rev_stack_param_offset(const rev_cfg* cfg, int32_t block, int32_t tensor, int64_t* count) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (block < 0 || block >= cfg->n_blocks || tensor < 0 || tensor >= T_COUNT) {
+        set_error("param_offset: block or tensor index out of range"); return REV_EINVAL;
+    }
+    if (count) *count = tensor_count(*cfg, tensor);
+    return block_params(*cfg) * block + tensor_offset(*cfg, tensor);
+}
+
+int64_t rev_stack_workspace_bytes(const rev_cfg* cfg) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    return make_layout(*cfg).total;
+}
+
+int rev_stack_forward(const rev_cfg* cfg, const void* params, const float* X1, const float* X2, float* Y1, float* Y2,
+                      void* ws, int64_t ws_bytes, void* stream) {
+    RC(check_common(cfg, ws, ws_bytes));
+    if (!params || !X1 || !X2 || !Y1 || !Y2) { set_error("a required pointer is null"); return REV_EINVAL; }
+    if (!aligned16(params) || !aligned16(X1) || !aligned16(X2) || !aligned16(Y1) || !aligned16(Y2)) {
+        set_error("every buffer must be 16-byte aligned"); return REV_EINVAL;
+    }
+    if (cfg->mode == REV_MODE_BF16) {
+        Runner<bf16> r(*cfg, params, nullptr, ws);
+        return r.forward(X1, X2, Y1, Y2, (hipStream_t)stream);
+    }
+    Runner<float> r(*cfg, params, nullptr, ws);
+    return r.forward(X1, X2, Y1, Y2, (hipStream_t)stream);
+}
+
+int rev_stack_backward_reprop(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
+                              const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1_out, float* X2_out,
+                              float* dparams, void* ws, int64_t ws_bytes, void* stream) {
+    return backward_entry(0, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws, ws_bytes, stream, stream);
+}
+
+int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
+                                const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1_out, float* X2_out,
+                                float* dparams, void* ws, int64_t ws_bytes, void* stream_grad, void* stream_recompute) {
+    return backward_entry(1, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws, ws_bytes,
+                          stream_grad, stream_recompute);
+}
+
+int rev_stack_backward_chain(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
+                             const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1_out, float* X2_out,
+                             float* dparams, void* ws, int64_t ws_bytes, void* stream, int32_t chain) {
+    if (chain != 0 && chain != 1) { set_error("chain must be 0 or 1"); return REV_EINVAL; }
+    return backward_entry(chain == 0 ? 2 : 3, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws,
+                          ws_bytes, stream, stream);
+}
+
+int rev_profile_begin(void) {
+    for (auto& r : g_prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+    g_prof_recs.clear();
+    for (int k = 0; k < K_COUNT; ++k) { g_prof_ms[k] = 0; g_prof_n[k] = 0; g_prof_work[k] = 0; }
+    g_prof_on = true;
+    return REV_OK;
+}
+
+int rev_profile_end(void) {
+    g_prof_on = false;
+    REV_HIP(hipDeviceSynchronize());
+    for (auto& r : g_prof_recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) { g_prof_ms[r.kind] += ms; g_prof_n[r.kind] += 1; }
+        (void)hipEventDestroy(r.e0);
+        (void)hipEventDestroy(r.e1);
+    }
+    g_prof_recs.clear();
+    return REV_OK;
+}
+
+int rev_profile_kinds(void) { return K_COUNT; }
+const char* rev_profile_name(int kind) { return (kind >= 0 && kind < K_COUNT) ? g_kind_names[kind] : ""; }
+int rev_profile_is_flops(int kind) { return (kind >= 0 && kind < K_COUNT) ? g_kind_flops[kind] : 0; }
+int rev_profile_get(int kind, double* total_ms, int64_t* launches, double* work) {
+    if (kind < 0 || kind >= K_COUNT) { set_error("profile_get: bad kind"); return REV_EINVAL; }
+    if (total_ms) *total_ms = g_prof_ms[kind];
+    if (launches) *launches = g_prof_n[kind];
+    if (work) *work = g_prof_work[kind];
+    return REV_OK;
+}
+
+const char* rev_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"

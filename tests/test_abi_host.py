@@ -1,0 +1,90 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, sizes the packed parameters as the layout
+says, and rejects bad arguments before enqueuing anything."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2306_09342_amd import binding as B
+from paper_2306_09342_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_functions():
+    text = open(os.path.join(ROOT, "include", "rev_stack.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rev_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = _header_functions()
+    assert "rev_stack_forward" in names and "rev_stack_backward_pareprop" in names
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_param_count_and_offsets_match_the_layout(name):
+    cfg = synth.CONFIGS[name]
+    c = B.make_cfg(**cfg)
+    D, Dm, N = cfg["d_model"], cfg["d_mlp"], cfg["n_blocks"]
+    per = 4 * D * D + 2 * D * Dm + 9 * D + Dm
+    assert B.rev_stack_param_count(c) == N * per == N * synth.params_per_block(D, Dm)
+    off = 0
+    for t, (tname, shape) in enumerate(synth.block_tensors(D, Dm)):
+        o, cnt = B.rev_stack_param_offset(c, N - 1, t)
+        assert o == (N - 1) * per + off and cnt == int(np.prod(shape)), tname
+        off += cnt
+    ws = B.rev_stack_workspace_bytes(c)
+    assert ws > 0 and ws % 256 == 0
+
+
+def test_bad_configs_are_rejected():
+    good = dict(synth.CONFIGS["tiny"])
+    assert B.rev_stack_check_cfg(B.make_cfg(**good)) == 0
+    for key, val in (("n_blocks", 0), ("d_model", 60), ("n_heads", 3), ("d_mlp", 100), ("seq_len", -1),
+                     ("batch", 0), ("mode", 7), ("n_heads", 16), ("ln_eps", -1.0), ("d_model", 16384)):
+        bad = dict(good)
+        bad[key] = val
+        c = B.make_cfg(**bad)
+        assert B.rev_stack_check_cfg(c) == -1, (key, val)
+        assert B.rev_last_error() != ""
+        with pytest.raises(B.RevError):
+            B.rev_stack_workspace_bytes(c)
+    assert B.lib().rev_stack_check_cfg(None) == -1
+    # head_dim above 128
+    c = B.make_cfg(n_blocks=1, d_model=512, n_heads=2, d_mlp=512, seq_len=4, batch=1)
+    assert B.rev_stack_check_cfg(c) == -1
+
+
+def test_null_pointers_and_short_workspace_fail_before_any_gpu_work():
+    L = B.lib()
+    c = B.make_cfg(**synth.CONFIGS["tiny"])
+    need = B.rev_stack_workspace_bytes(c)
+    fake = ctypes.c_void_p(0x10000)          # never dereferenced: validation comes first
+    vp = ctypes.c_void_p
+    # null workspace
+    assert L.rev_stack_forward(ctypes.byref(c), fake, fake, fake, fake, fake, None, need, None) == -1
+    # short workspace
+    assert L.rev_stack_forward(ctypes.byref(c), fake, fake, fake, fake, fake, fake, need - 1, None) == -2
+    assert "workspace too small" in B.rev_last_error()
+    # null tensors
+    assert L.rev_stack_forward(ctypes.byref(c), None, fake, fake, fake, fake, fake, need, None) == -1
+    args = [ctypes.byref(c), fake, fake, fake, fake, fake, fake, fake, None, None, None, fake, need]
+    assert L.rev_stack_backward_reprop(*args, None) == -1            # dparams null
+    args[10] = fake
+    args[2] = vp(0x10004)                                             # misaligned Y1
+    assert L.rev_stack_backward_reprop(*args, None) == -1
+    args[2] = fake
+    s = vp(0x1234)
+    assert L.rev_stack_backward_pareprop(*args, s, s) == -1           # same stream twice
+    assert "different streams" in B.rev_last_error()
+    assert L.rev_stack_backward_chain(*args, None, 5) == -1
+    assert L.rev_profile_kinds() >= 6
+    assert L.rev_profile_name(0) == b"gemm_nt"

@@ -1,0 +1,116 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the fp64
+CPU oracle on the same seeded inputs.  Tolerances and the error measure are in
+parity_util (1e-4 float32 mode, 3e-2 bf16 mode, max-abs error over max-abs
+reference, per tensor).  PaReprop must equal Reprop bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rev_oracle as O
+from paper_2306_09342_amd import binding as B
+from paper_2306_09342_amd import synth
+
+from parity_util import TOL, compare_backward, gpu_cfg, make_case, oracle_forward, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+# small shapes that still span several tiles and ragged tails: M = B*T is not a
+# multiple of 64, T is odd, head_dim 64 / 80 / 32 / 128
+SHAPES = {
+    "tiny": dict(synth.CONFIGS["tiny"]),
+    "ragged_dh64": dict(n_blocks=2, d_model=128, n_heads=2, d_mlp=512, seq_len=77, batch=3),
+    "ragged_dh80": dict(n_blocks=2, d_model=160, n_heads=2, d_mlp=328, seq_len=51, batch=2),
+    "dh128_T1": dict(n_blocks=2, d_model=256, n_heads=2, d_mlp=264, seq_len=1, batch=5),
+    "vit_s_slice": dict(n_blocks=3, d_model=384, n_heads=6, d_mlp=1536, seq_len=197, batch=3),
+    "one_sample_T300": dict(n_blocks=1, d_model=64, n_heads=2, d_mlp=64, seq_len=300, batch=1),
+}
+
+
+def _run_case(name, mode, seed=0):
+    cfg = dict(SHAPES[name])
+    cfg["mode"] = mode
+    print(f"[case] {name} mode={mode} seed={seed} cfg={cfg}", flush=True)
+    flat, blocks, x, dy1, dy2 = make_case(cfg, seed=seed)
+    x2 = x[:, ::-1].copy()                      # distinct streams so a swap shows
+    H = cfg["n_heads"]
+    y1, y2 = oracle_forward(cfg, blocks, x, x2)
+    y1f, y2f = y1.astype(np.float32), y2.astype(np.float32)
+    ref = O.stack_backward_reversible_chunked(y1f, y2f, blocks, H, dy1, dy2)
+
+    c = gpu_cfg(cfg)
+    params = to_dev(flat, B.param_dtype(c))
+    ws = B.alloc_workspace(c)
+    # forward parity
+    gy1, gy2 = B.rev_stack_forward(c, params, to_dev(x), to_dev(x2), workspace=ws)
+    torch.cuda.synchronize()
+    tol = TOL[mode]
+    assert rel_err(gy1.cpu().numpy(), y1) <= tol and rel_err(gy2.cpu().numpy(), y2) <= tol
+    # backward parity, both schedules
+    dY1, dY2, Y1, Y2 = to_dev(dy1), to_dev(dy2), to_dev(y1f), to_dev(y2f)
+    rep = B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws, want_inputs=True)
+    torch.cuda.synchronize()
+    worst = compare_backward(cfg, rep, ref, tol, what=f"{name}/{mode}/reprop")
+    side = torch.cuda.Stream()
+    par = B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side, workspace=ws, want_inputs=True)
+    torch.cuda.synchronize()
+    for k in ("dX1", "dX2", "dparams", "X1", "X2"):
+        assert torch.equal(rep[k], par[k]), f"PaReprop differs from Reprop in {k}"
+    # the reconstructed inputs are the true inputs
+    assert rel_err(rep["X1"].cpu().numpy(), x) <= tol and rel_err(rep["X2"].cpu().numpy(), x2) <= tol
+    print(f"[ok] {name}/{mode}: worst {max(worst.values()):.3e} at {max(worst, key=worst.get)}", flush=True)
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_fp32_mode_matches_oracle(name):
+    _run_case(name, "fp32")
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_bf16_mode_matches_oracle(name):
+    _run_case(name, "bf16")
+
+
+def test_paper_recipe_inputs_tiny_fp32():
+    """The tiny config exactly as specified: X duplicated to both streams, unit
+    gains, zero biases, seed 0."""
+    cfg = dict(synth.CONFIGS["tiny"])
+    flat = synth.make_params(cfg, seed=0)
+    x, dy1, dy2 = synth.make_inputs(cfg, seed=0)
+    blocks = O.unpack_params(flat, cfg["n_blocks"], cfg["d_model"], cfg["d_mlp"])
+    y1, y2 = oracle_forward(cfg, blocks, x, x)
+    y1f, y2f = y1.astype(np.float32), y2.astype(np.float32)
+    ref = O.stack_backward_reversible_chunked(y1f, y2f, blocks, cfg["n_heads"], dy1, dy2)
+    c = gpu_cfg(cfg)
+    res = B.rev_stack_backward_reprop(c, to_dev(flat), to_dev(y1f), to_dev(y2f), to_dev(dy1), to_dev(dy2),
+                                      want_inputs=True)
+    torch.cuda.synchronize()
+    compare_backward(cfg, res, ref, TOL["fp32"], what="tiny recipe")
+
+
+def test_outputs_do_not_depend_on_stale_workspace_or_repeat():
+    """Two calls in a row on a workspace filled with NaN bytes give identical bits."""
+    cfg = dict(SHAPES["ragged_dh64"], mode="bf16")
+    flat, blocks, x, dy1, dy2 = make_case(cfg, seed=3)
+    c = gpu_cfg(cfg)
+    params = to_dev(flat, B.param_dtype(c))
+    ws = B.alloc_workspace(c)
+    Y1, Y2 = B.rev_stack_forward(c, params, to_dev(x), to_dev(x), workspace=ws)
+    ws.fill_(0xFF)
+    a = B.rev_stack_backward_reprop(c, params, Y1, Y2, to_dev(dy1), to_dev(dy2), workspace=ws)
+    torch.cuda.synchronize()
+    ws.fill_(0x7F)
+    side = torch.cuda.Stream()
+    b = B.rev_stack_backward_pareprop(c, params, Y1, Y2, to_dev(dy1), to_dev(dy2), side, workspace=ws)
+    torch.cuda.synchronize()
+    for k in ("dX1", "dX2", "dparams"):
+        assert torch.isfinite(a[k]).all()
+        assert torch.equal(a[k], b[k]), k
+
+
+def test_short_workspace_is_an_error_on_the_gpu_too():
+    cfg = dict(SHAPES["tiny"])
+    c = gpu_cfg(cfg)
+    flat, _, x, _, _ = make_case(cfg)
+    ws = torch.empty(B.rev_stack_workspace_bytes(c) - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.RevError, match="workspace too small"):
+        B.rev_stack_forward(c, to_dev(flat), to_dev(x), to_dev(x), workspace=ws)
