@@ -213,12 +213,42 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
     *reinterpret_cast<float4*>(out + 4 * i) = acc;
 }
 
+// Same sum for many partial rows: 16 row-lanes per column group walk the rows
+// p = lane, lane+16, ... and are folded in lane order through LDS.
+__global__ __launch_bounds__(256) void reduce_rows_wide_kernel(const float* __restrict__ partial, int P,
+                                                               int64_t stride, int64_t n4, float* __restrict__ out) {
+    __shared__ float4 sh[256];
+    const int cg = threadIdx.x & 15, pl = threadIdx.x >> 4;
+    const int64_t i = (int64_t)blockIdx.x * 16 + cg;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n4) {
+        for (int p = pl; p < P; p += 16) {
+            float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * stride + 4 * i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    }
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    if (pl == 0 && i < n4) {
+        for (int q = 1; q < 16; ++q) {
+            float4 v = sh[q * 16 + cg];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<float4*>(out + 4 * i) = acc;
+    }
+}
+
 int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out) {
     if (n % 4 != 0) { set_error("reduce_rows: length must be a multiple of 4"); return REV_EINVAL; }
     ProfScope ps(K_REDUCE, s, (double)(P + 1) * n * 4);
     int64_t n4 = n / 4;
-    dim3 grid((unsigned)((n4 + 255) / 256)), block(256);
-    hipLaunchKernelGGL(reduce_rows_kernel, grid, block, 0, s, partial, P, stride, n4, out);
+    if (P > 32) {
+        hipLaunchKernelGGL(reduce_rows_wide_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, s, partial, P,
+                           stride, n4, out);
+    } else {
+        hipLaunchKernelGGL(reduce_rows_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, partial, P,
+                           stride, n4, out);
+    }
     REV_HIP(hipGetLastError());
     return REV_OK;
 }

@@ -1,15 +1,369 @@
-// bf16 matrix-core GEMMs (placeholder dispatch: plain kernels until the MFMA path lands)
+// bf16 matrix-core GEMMs for gfx950 (v_mfma_f32_32x32x16_bf16, float32 accumulate).
+//
+//  gemm_nt   C[M,N] = A[M,K] * B[N,K]^T      both operands contraction-contiguous;
+//            LDS tiles keep the global layout, fragments are 16-byte LDS reads.
+//  wgrad     dW[N,K] = G[M,N]^T * A[M,K]     both operands have the contraction
+//            index (the token) as the slow one; tiles are stored in LDS as they
+//            come from HBM and fragments are read with the LDS transpose read
+//            (ds_read_b64_tr_b16), so no operand is ever transposed in memory.
+//            The token reduction is split into a fixed number of ranges whose
+//            partial tiles are summed afterwards in range order: results do not
+//            depend on scheduling.
+//
+// Register layout of the 32x32x16 instruction, per lane l of the wavefront:
+//   A operand: row l%32, k = 8*(l/32) .. +7;  B operand: column l%32, same k;
+//   D: column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for accumulator register v.
 #include "common.h"
+
 namespace rev {
-int64_t wgrad_partial_elems(int M, int N, int K) { (void)M; (void)N; (void)K; return 64; }
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+// Workgroups go round-robin over the 8 XCDs, each with its own L2: give every
+// XCD one contiguous run of tiles so that neighbouring tiles (which share an
+// operand panel) meet in the same L2.
+__device__ __forceinline__ int xcd_remap(int b, int nblk) {
+    const int per = nblk >> 3;
+    if (b >= per * 8) return b;
+    return (b & 7) * per + (b >> 3);
+}
+
+// ----------------------------------------------------------------------------------------
+// epilogues (compile-time kind); m, n are global indices, acc the float32 sum
+// ----------------------------------------------------------------------------------------
+template <int KIND>
+__device__ __forceinline__ void epi_store(const Epi& e, int m, int n, float acc, float biasv) {
+    const int64_t idx = (int64_t)m * e.ldo + n;
+    if (KIND == EPI_BIAS) {
+        reinterpret_cast<bf16*>(e.out)[idx] = __float2bfloat16(acc + biasv);
+    } else if (KIND == EPI_BIAS_GELU) {
+        float h = acc + biasv;
+        reinterpret_cast<bf16*>(e.out)[idx] = __float2bfloat16(h);
+        reinterpret_cast<bf16*>(e.out2)[idx] = __float2bfloat16(gelu_f(h));
+    } else if (KIND == EPI_RESIDUAL) {
+        e.outf[idx] = e.res[idx] + e.sign * (acc + biasv);
+    } else if (KIND == EPI_GELU_BWD) {
+        float h = __bfloat162float(reinterpret_cast<const bf16*>(e.aux)[idx]);
+        reinterpret_cast<bf16*>(e.out)[idx] = __float2bfloat16(acc * gelu_grad_f(h));
+    } else if (KIND == EPI_PLAIN) {
+        reinterpret_cast<bf16*>(e.out)[idx] = __float2bfloat16(acc);
+    } else {
+        e.outf[idx] = acc;
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// NT GEMM
+// ----------------------------------------------------------------------------------------
+constexpr int NT_BK = 64;
+constexpr int NT_LDP = NT_BK + 8;     // LDS row pitch in elements (144 B: 16-byte rows land on distinct banks)
+
+template <int BM, int BN, int WM, int WN, int KIND>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(const bf16* __restrict__ A, int64_t lda,
+                                                                const bf16* __restrict__ B, int64_t ldb,
+                                                                int M, int N, int K, Epi epi) {
+    constexpr int NTH = WM * WN * 64;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int CA = BM * (NT_BK / 8) / NTH, CB = BN * (NT_BK / 8) / NTH;
+    static_assert(CA * NTH == BM * (NT_BK / 8) && CB * NTH == BN * (NT_BK / 8), "tile/thread mismatch");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem);                 // [2][BM][LDP]
+    uint16_t* Bs = As + 2 * BM * NT_LDP;                              // [2][BN][LDP]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int tiles_n = (N + BN - 1) / BN;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    uint4 ra[CA], rb[CB];
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    auto gload = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) {
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
+            const int gk = kt * NT_BK + ch * 8;
+            const int gr = min(m0 + row, M - 1);
+            ra[i] = (gk < K) ? *reinterpret_cast<const uint4*>(A + (int64_t)gr * lda + gk) : zero4;
+        }
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
+            const int gk = kt * NT_BK + ch * 8;
+            const int gr = min(n0 + row, N - 1);
+            rb[i] = (gk < K) ? *reinterpret_cast<const uint4*>(B + (int64_t)gr * ldb + gk) : zero4;
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) {
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
+            *reinterpret_cast<uint4*>(As + (buf * BM + row) * NT_LDP + ch * 8) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
+            *reinterpret_cast<uint4*>(Bs + (buf * BN + row) * NT_LDP + ch * 8) = rb[i];
+        }
+    };
+
+    const int nk = (K + NT_BK - 1) / NT_BK;
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) gload(kt + 1);
+        const uint16_t* Ab = As + (buf * BM + wm * TM * 32 + fr) * NT_LDP + fk;
+        const uint16_t* Bb = Bs + (buf * BN + wn * TN * 32 + fr) * NT_LDP + fk;
+#pragma unroll
+        for (int kk = 0; kk < NT_BK / 16; ++kk) {
+            bf16x8_t a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(Ab + i * 32 * NT_LDP + kk * 16);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(Bb + j * 32 * NT_LDP + kk * 16);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) lstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue straight from the accumulator layout
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * TN * 32 + j * 32 + (lane & 31);
+        if (n >= N) continue;
+        float biasv = 0.f;
+        if (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL)
+            biasv = __bfloat162float(reinterpret_cast<const bf16*>(epi.bias)[n]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mb = m0 + wm * TM * 32 + i * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = mb + 8 * (v >> 2) + (v & 3);
+                if (m < M) epi_store<KIND>(epi, m, n, acc[i][j][v], biasv);
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int KIND>
+static int launch_nt(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
+                     const Epi& epi) {
+    constexpr size_t shmem = (size_t)2 * (BM + BN) * NT_LDP * sizeof(uint16_t);
+    static bool attr_set = false;
+    auto kern = gemm_nt_kernel<BM, BN, WM, WN, KIND>;
+    if (!attr_set) {
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
+        attr_set = true;
+    }
+    const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(WM * WN * 64), shmem, s, A, lda, B, ldb, M, N, K, epi);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
 int gemm_nt_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
                  int M, int N, int K, const Epi& epi) {
-    return gemm_nt_bf16_simple(s, A, lda, B, ldb, M, N, K, epi);
+    if ((lda & 7) || (ldb & 7) || (K & 7) || ((uintptr_t)A & 15) || ((uintptr_t)B & 15)) {
+        return gemm_nt_bf16_simple(s, A, lda, B, ldb, M, N, K, epi);
+    }
+    ProfScope ps(K_GEMM_NT, s, 2.0 * M * N * K);
+    switch (epi.kind) {
+#define CASE(KIND) case KIND: return launch_nt<128, 128, 2, 2, KIND>(s, A, lda, B, ldb, M, N, K, epi);
+        CASE(EPI_BIAS) CASE(EPI_BIAS_GELU) CASE(EPI_RESIDUAL) CASE(EPI_GELU_BWD) CASE(EPI_PLAIN) CASE(EPI_PLAIN_F32)
+#undef CASE
+    }
+    set_error("gemm_nt_bf16: unknown epilogue");
+    return REV_EINVAL;
 }
+
+// ----------------------------------------------------------------------------------------
+// weight gradient: dW[N,K] = sum over tokens m of G[m,n] * A[m,k]
+// ----------------------------------------------------------------------------------------
+constexpr int WG_BP = 128;            // tile rows (n)
+constexpr int WG_BQ = 128;            // tile cols (k)
+constexpr int WG_BR = 64;             // tokens per step
+constexpr int WG_LDP = 128 + 32;      // LDS pitch in elements (320 B)
+
+// LDS transpose read: the 16 lanes of a group hand in 4x4 row chunks (4 rows r, 4
+// chunks of 4 columns) and lane j of the group receives column j of those rows,
+// i.e. 4 consecutive r for its own column.
+__device__ __forceinline__ s16x4_t lds_tr16(const uint16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, p));
+}
+
+// fragment for rows/cols c0..c0+31 of the tile and the 16 tokens r0..r0+15
+__device__ __forceinline__ bf16x8_t tr_frag(const uint16_t* tile, int pitch, int r0, int c0, int lane) {
+    const int j = lane & 15, g = lane >> 4;
+    const int c = c0 + (g & 1) * 16 + 4 * (j & 3);
+    const int r = r0 + (g >> 1) * 8 + (j >> 2);
+    const uint16_t* p = tile + r * pitch + c;
+    s16x4_t lo = lds_tr16(p);
+    s16x4_t hi = lds_tr16(p + 4 * pitch);
+    union { struct { s16x4_t lo, hi; } s; bf16x8_t v; } u;
+    u.s.lo = lo;
+    u.s.hi = hi;
+    return u.v;
+}
+
+static int wgrad_splits(int M, int N, int K) {
+    const int tiles = ((N + WG_BP - 1) / WG_BP) * ((K + WG_BQ - 1) / WG_BQ);
+    int S = (512 + tiles - 1) / tiles;
+    const int steps = (M + WG_BR - 1) / WG_BR;
+    if (S > steps) S = steps;
+    if (S > 16) S = 16;
+    if (S < 1) S = 1;
+    return S;
+}
+int64_t wgrad_partial_elems(int M, int N, int K) {
+    const int S = wgrad_splits(M, N, K);
+    return S > 1 ? (int64_t)S * N * K : 0;
+}
+
+__global__ __launch_bounds__(256) void wgrad_kernel(const bf16* __restrict__ G, int64_t ldg,
+                                                    const bf16* __restrict__ A, int64_t lda,
+                                                    int M, int N, int K, int steps_per_split,
+                                                    float* __restrict__ out, int64_t split_stride) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* Gs = reinterpret_cast<uint16_t*>(smem);              // [2][WG_BR][WG_LDP]
+    uint16_t* As = Gs + 2 * WG_BR * WG_LDP;                        // [2][WG_BR][WG_LDP]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wp = wave >> 1, wq = wave & 1;                       // 2 x 2 wavefronts, 64 x 64 each
+    const int tiles_q = (K + WG_BQ - 1) / WG_BQ;
+    const int tiles = ((N + WG_BP - 1) / WG_BP) * tiles_q;
+    const int split = blockIdx.x / tiles;
+    const int tile = xcd_remap(blockIdx.x % tiles, tiles);
+    const int p0 = (tile / tiles_q) * WG_BP, q0 = (tile % tiles_q) * WG_BQ;
+    const int step0 = split * steps_per_split;
+    const int nsteps = min(steps_per_split, (M + WG_BR - 1) / WG_BR - step0);
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // 64 tokens x 16 chunks of 8 columns per operand tile = 1024 chunks, 4 per thread
+    uint4 rg[4], ra[4];
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    auto gload = [&](int st) {
+        const int mbase = (step0 + st) * WG_BR;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;
+            const int m = mbase + row;
+            const int gp = p0 + ch * 8, gq = q0 + ch * 8;
+            rg[i] = (m < M && gp < N) ? *reinterpret_cast<const uint4*>(G + (int64_t)m * ldg + gp) : zero4;
+            ra[i] = (m < M && gq < K) ? *reinterpret_cast<const uint4*>(A + (int64_t)m * lda + gq) : zero4;
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;
+            *reinterpret_cast<uint4*>(Gs + (buf * WG_BR + row) * WG_LDP + ch * 8) = rg[i];
+            *reinterpret_cast<uint4*>(As + (buf * WG_BR + row) * WG_LDP + ch * 8) = ra[i];
+        }
+    };
+
+    if (nsteps > 0) {
+        gload(0);
+        lstore(0);
+    }
+    __syncthreads();
+    for (int st = 0; st < nsteps; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < nsteps) gload(st + 1);
+        const uint16_t* Gt = Gs + buf * WG_BR * WG_LDP;
+        const uint16_t* At = As + buf * WG_BR * WG_LDP;
+#pragma unroll
+        for (int kk = 0; kk < WG_BR / 16; ++kk) {
+            bf16x8_t a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = tr_frag(Gt, WG_LDP, kk * 16, wp * 64 + i * 32, lane);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = tr_frag(At, WG_LDP, kk * 16, wq * 64 + j * 32, lane);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (st + 1 < nsteps) lstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    float* o = out + (int64_t)split * split_stride;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int q = q0 + wq * 64 + j * 32 + (lane & 31);
+        if (q >= K) continue;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int pb = p0 + wp * 64 + i * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int p = pb + 8 * (v >> 2) + (v & 3);
+                if (p < N) o[(int64_t)p * K + q] = acc[i][j][v];
+            }
+        }
+    }
+}
+
 int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
-                    int M, int N, int K, float* dW, float*, int64_t) {
-    return gemm_wgrad_bf16_simple(s, G, ldg, A, lda, M, N, K, dW);
+                    int M, int N, int K, float* dW, float* partial, int64_t partial_elems) {
+    if ((ldg & 7) || (lda & 7) || (N & 7) || (K & 7) || ((uintptr_t)G & 15) || ((uintptr_t)A & 15)) {
+        return gemm_wgrad_bf16_simple(s, G, ldg, A, lda, M, N, K, dW);
+    }
+    const int S = wgrad_splits(M, N, K);
+    if (S > 1 && (partial == nullptr || partial_elems < (int64_t)S * N * K)) {
+        set_error("gemm_wgrad_bf16: split scratch too small");
+        return REV_EWORKSPACE;
+    }
+    const int steps = (M + WG_BR - 1) / WG_BR;
+    const int sps = (steps + S - 1) / S;
+    const int tiles = ((N + WG_BP - 1) / WG_BP) * ((K + WG_BQ - 1) / WG_BQ);
+    constexpr size_t shmem = (size_t)4 * WG_BR * WG_LDP * sizeof(uint16_t);
+    static bool attr_set = false;
+    if (!attr_set) {
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
+        attr_set = true;
+    }
+    {
+        ProfScope ps(K_GEMM_WGRAD, s, 2.0 * M * N * K);
+        hipLaunchKernelGGL(wgrad_kernel, dim3(tiles * S), dim3(256), shmem, s, G, ldg, A, lda, M, N, K, sps,
+                           S > 1 ? partial : dW, (int64_t)N * K);
+        REV_HIP(hipGetLastError());
+    }
+    if (S > 1) return reduce_rows(s, partial, S, (int64_t)N * K, (int64_t)N * K, dW);
+    return REV_OK;
 }
+
+// ----------------------------------------------------------------------------------------
+// attention dispatch (plain kernels until the matrix-core versions take over)
+// ----------------------------------------------------------------------------------------
 template <typename TA>
 int attention_forward(hipStream_t s, const TA* qkv, TA* o, float* lse, int B, int T, int H, int dh) {
     return attention_forward_simple<TA>(s, qkv, o, lse, B, T, H, dh);
@@ -23,4 +377,5 @@ template int attention_forward<float>(hipStream_t, const float*, float*, float*,
 template int attention_forward<bf16>(hipStream_t, const bf16*, bf16*, float*, int, int, int, int);
 template int attention_backward<float>(hipStream_t, const float*, const float*, const float*, const float*, float*, float*, int, int, int, int);
 template int attention_backward<bf16>(hipStream_t, const bf16*, const bf16*, const bf16*, const float*, bf16*, float*, int, int, int, int);
-}
+
+}  // namespace rev
