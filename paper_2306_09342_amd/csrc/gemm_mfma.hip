@@ -20,6 +20,7 @@ namespace rev {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -88,45 +89,43 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(const bf16* __res
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 ra[CA], rb[CB];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < CA; ++i) {
-            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
-            const int gk = kt * NT_BK + ch * 8;
-            const int gr = min(m0 + row, M - 1);
-            ra[i] = (gk < K) ? *reinterpret_cast<const uint4*>(A + (int64_t)gr * lda + gk) : zero4;
-        }
-#pragma unroll
-        for (int i = 0; i < CB; ++i) {
-            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
-            const int gk = kt * NT_BK + ch * 8;
-            const int gr = min(n0 + row, N - 1);
-            rb[i] = (gk < K) ? *reinterpret_cast<const uint4*>(B + (int64_t)gr * ldb + gk) : zero4;
-        }
-    };
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < CA; ++i) {
-            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
-            *reinterpret_cast<uint4*>(As + (buf * BM + row) * NT_LDP + ch * 8) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < CB; ++i) {
-            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;
-            *reinterpret_cast<uint4*>(Bs + (buf * BN + row) * NT_LDP + ch * 8) = rb[i];
-        }
-    };
+    u32x4_t ra[CA], rb[CB];
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+#define NT_GLOAD(kt)                                                                                   \
+    {                                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < CA; ++i) {                                               \
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;                               \
+            const int gk = (kt) * NT_BK + ch * 8;                                                      \
+            const int gr = min(m0 + row, M - 1);                                                       \
+            ra[i] = (gk < K) ? *reinterpret_cast<const u32x4_t*>(A + (int64_t)gr * lda + gk) : zero4;    \
+        }                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < CB; ++i) {                                               \
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;                               \
+            const int gk = (kt) * NT_BK + ch * 8;                                                      \
+            const int gr = min(n0 + row, N - 1);                                                       \
+            rb[i] = (gk < K) ? *reinterpret_cast<const u32x4_t*>(B + (int64_t)gr * ldb + gk) : zero4;    \
+        }                                                                                              \
+    }
+#define NT_LSTORE(buf)                                                                                 \
+    {                                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < CA; ++i) {                                               \
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;                               \
+            *reinterpret_cast<u32x4_t*>(As + ((buf) * BM + row) * NT_LDP + ch * 8) = ra[i];              \
+        }                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < CB; ++i) {                                               \
+            const int idx = tid + i * NTH, row = idx >> 3, ch = idx & 7;                               \
+            *reinterpret_cast<u32x4_t*>(Bs + ((buf) * BN + row) * NT_LDP + ch * 8) = rb[i];              \
+        }                                                                                              \
+    }
 
     const int nk = (K + NT_BK - 1) / NT_BK;
-    gload(0);
-    lstore(0);
+    NT_GLOAD(0);
+    NT_LSTORE(0);
     __syncthreads();
     const int fr = lane & 31, fk = (lane >> 5) * 8;
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1);
+        if (kt + 1 < nk) NT_GLOAD(kt + 1);
         const uint16_t* Ab = As + (buf * BM + wm * TM * 32 + fr) * NT_LDP + fk;
         const uint16_t* Bb = Bs + (buf * BN + wn * TN * 32 + fr) * NT_LDP + fk;
 #pragma unroll
@@ -142,7 +141,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(const bf16* __res
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) lstore(buf ^ 1);
+        if (kt + 1 < nk) NT_LSTORE(buf ^ 1);
         __syncthreads();
     }
 
@@ -266,36 +265,36 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const bf16* __restrict__ G, 
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // 64 tokens x 16 chunks of 8 columns per operand tile = 1024 chunks, 4 per thread
-    uint4 rg[4], ra[4];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    auto gload = [&](int st) {
-        const int mbase = (step0 + st) * WG_BR;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;
-            const int m = mbase + row;
-            const int gp = p0 + ch * 8, gq = q0 + ch * 8;
-            rg[i] = (m < M && gp < N) ? *reinterpret_cast<const uint4*>(G + (int64_t)m * ldg + gp) : zero4;
-            ra[i] = (m < M && gq < K) ? *reinterpret_cast<const uint4*>(A + (int64_t)m * lda + gq) : zero4;
-        }
-    };
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;
-            *reinterpret_cast<uint4*>(Gs + (buf * WG_BR + row) * WG_LDP + ch * 8) = rg[i];
-            *reinterpret_cast<uint4*>(As + (buf * WG_BR + row) * WG_LDP + ch * 8) = ra[i];
-        }
-    };
+    u32x4_t rg[4], ra[4];
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+#define WG_GLOAD(st)                                                                                             \
+    {                                                                                                            \
+        const int mbase = (step0 + (st)) * WG_BR;                                                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                          \
+            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;                                        \
+            const int m = mbase + row;                                                                           \
+            const int gp = p0 + ch * 8, gq = q0 + ch * 8;                                                        \
+            rg[i] = (m < M && gp < N) ? *reinterpret_cast<const u32x4_t*>(G + (int64_t)m * ldg + gp) : zero4;      \
+            ra[i] = (m < M && gq < K) ? *reinterpret_cast<const u32x4_t*>(A + (int64_t)m * lda + gq) : zero4;      \
+        }                                                                                                        \
+    }
+#define WG_LSTORE(buf)                                                                                           \
+    {                                                                                                            \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                          \
+            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;                                        \
+            *reinterpret_cast<u32x4_t*>(Gs + ((buf) * WG_BR + row) * WG_LDP + ch * 8) = rg[i];                     \
+            *reinterpret_cast<u32x4_t*>(As + ((buf) * WG_BR + row) * WG_LDP + ch * 8) = ra[i];                     \
+        }                                                                                                        \
+    }
 
     if (nsteps > 0) {
-        gload(0);
-        lstore(0);
+        WG_GLOAD(0);
+        WG_LSTORE(0);
     }
     __syncthreads();
     for (int st = 0; st < nsteps; ++st) {
         const int buf = st & 1;
-        if (st + 1 < nsteps) gload(st + 1);
+        if (st + 1 < nsteps) WG_GLOAD(st + 1);
         const uint16_t* Gt = Gs + buf * WG_BR * WG_LDP;
         const uint16_t* At = As + buf * WG_BR * WG_LDP;
 #pragma unroll
@@ -311,7 +310,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const bf16* __restrict__ G, 
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
-        if (st + 1 < nsteps) lstore(buf ^ 1);
+        if (st + 1 < nsteps) WG_LSTORE(buf ^ 1);
         __syncthreads();
     }
 
