@@ -1,0 +1,455 @@
+// bf16 softmax attention on the matrix cores: forward (flash-style, log-sum-exp
+// saved) and backward in two passes, each free of atomics so that every sum has
+// a fixed order:
+//   pass 1  one wavefront owns 32 query rows, streams key/value tiles:  dQ, delta
+//   pass 2  one wavefront owns 32 key rows, streams query/dO tiles:     dK, dV
+//
+// The score tile is always produced with the OWNED index on the accumulator's
+// column (lane) axis: S^T[key, q] in the forward and in pass 1, S[q, key] in
+// pass 2.  Row statistics of the owned index are then per-lane scalars, and the
+// probability tile, converted to bf16 where it sits, is directly the B operand
+// of the next product; the streamed operand of that product is read from its
+// row-major LDS tile with the LDS transpose read.  No tile is ever transposed
+// through memory or shuffled across lanes.
+#include "mfma.h"
+
+namespace rev {
+
+constexpr int AT_ROWS = 64;     // streamed rows per LDS tile
+
+template <int DHP> struct AtCfg {
+    static constexpr int KS = DHP / 16;          // contraction steps over the head dim
+    static constexpr int DT = DHP / 32;          // 32-wide output tiles over the head dim
+    static constexpr int PITCH = DHP + 8;        // LDS row pitch (elements)
+    static constexpr int CH = DHP / 8;           // 16-byte chunks per row
+};
+
+// B-operand fragments of 32 owned rows straight from global memory:
+// lane (r = l%32, g) takes X[row0 + r][16*ks + 8g .. +7]; rows are clamped, columns >= dh read as zero.
+template <int DHP>
+__device__ __forceinline__ void load_owned(const bf16* __restrict__ base, int64_t ld, int row0, int nrows, int dh,
+                                           int lane, bf16x8_t (&frag)[DHP / 16]) {
+    const int r = min(row0 + (lane & 31), nrows - 1);
+    const bf16* p = base + (int64_t)r * ld + 8 * (lane >> 5);
+#pragma unroll
+    for (int ks = 0; ks < DHP / 16; ++ks) {
+        const int c = 16 * ks + 8 * (lane >> 5);
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (c < dh) v = *reinterpret_cast<const u32x4_t*>(p + 16 * ks);
+        union { u32x4_t u; bf16x8_t b; } cv;
+        cv.u = v;
+        frag[ks] = cv.b;
+    }
+}
+
+// Cooperative load of AT_ROWS rows [row0, row0+64) of a [nrows, ld] matrix into an LDS tile;
+// rows >= nrows and columns >= dh are zero-filled.
+template <int DHP>
+__device__ __forceinline__ void load_tile(uint16_t* tile, const bf16* __restrict__ base, int64_t ld, int row0,
+                                          int nrows, int dh) {
+    constexpr int CH = AtCfg<DHP>::CH, PITCH = AtCfg<DHP>::PITCH;
+    for (int idx = threadIdx.x; idx < AT_ROWS * CH; idx += blockDim.x) {
+        const int row = idx / CH, ch = idx % CH;
+        const int gr = row0 + row;
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (gr < nrows && ch * 8 < dh) v = *reinterpret_cast<const u32x4_t*>(base + (int64_t)gr * ld + ch * 8);
+        *reinterpret_cast<u32x4_t*>(tile + row * PITCH + ch * 8) = v;
+    }
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const float* p) {
+    bf16x8_t r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (__bf16)p[e];
+    return r;
+}
+
+__device__ __forceinline__ void store4_bf16(bf16* p, float a, float b, float c, float d) {
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    bf16x4_t v;
+    v[0] = (__bf16)a; v[1] = (__bf16)b; v[2] = (__bf16)c; v[3] = (__bf16)d;
+    *reinterpret_cast<bf16x4_t*>(p) = v;
+}
+
+// ----------------------------------------------------------------------------------------
+// forward
+// ----------------------------------------------------------------------------------------
+template <int DHP>
+__global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+                                                     float* __restrict__ lse, int T, int H, int dh) {
+    using C = AtCfg<DHP>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Vs = Ks + AT_ROWS * C::PITCH;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int g = lane >> 5;
+    const int bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int D = H * dh;
+    const int64_t ld = 3 * (int64_t)D;
+    const bf16* base = qkv + (int64_t)b * T * ld + h * dh;
+    const int q0 = (blockIdx.x * nw + wave) * 32;
+    const float scale = rsqrtf((float)dh);
+
+    bf16x8_t bq[C::KS];
+    load_owned<DHP>(base, ld, q0, T, dh, lane, bq);
+
+    f32x16_t accO[C::DT];
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accO[dt][v] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    for (int k0 = 0; k0 < T; k0 += AT_ROWS) {
+        __syncthreads();
+        load_tile<DHP>(Ks, base + D, ld, k0, T, dh);
+        load_tile<DHP>(Vs, base + 2 * D, ld, k0, T, dh);
+        __syncthreads();
+        const int nt = (T - k0 > 32) ? 2 : 1;
+        float s[2][16];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (t < nt) {
+                f32x16_t acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+                const uint16_t* kp = Ks + (t * 32 + (lane & 31)) * C::PITCH + 8 * g;
+#pragma unroll
+                for (int ks = 0; ks < C::KS; ++ks)
+                    acc = mfma32(*reinterpret_cast<const bf16x8_t*>(kp + 16 * ks), bq[ks], acc);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    s[t][v] = (key < T) ? acc[v] * scale : -INFINITY;
+                    mloc = fmaxf(mloc, s[t][v]);
+                }
+            }
+        }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        const float mn = fmaxf(m, mloc);
+        const float corr = __expf(m - mn);
+        float lsum = 0.f;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+            if (t < nt) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    s[t][v] = __expf(s[t][v] - mn);
+                    lsum += s[t][v];
+                }
+            }
+        lsum += __shfl_xor(lsum, 32, 64);
+        l = l * corr + lsum;
+        m = mn;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) accO[dt][v] *= corr;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+            if (t < nt) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const bf16x8_t pb = pack8(&s[t][8 * c]);
+#pragma unroll
+                    for (int dt = 0; dt < C::DT; ++dt) {
+                        const bf16x8_t a = tr_frag<4, 8>(Vs, C::PITCH, t * 32 + 16 * c, dt * 32, lane);
+                        accO[dt] = mfma32(a, pb, accO[dt]);
+                    }
+                }
+            }
+    }
+    // O^T tile: lane holds query q0 + l%32, features dt*32 + 8*(v/4) + 4g + v%4
+    const int q = q0 + (lane & 31);
+    if (q < T) {
+        const float inv = 1.f / l;
+        bf16* orow = o + ((int64_t)b * T + q) * D + h * dh;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int d = dt * 32 + 8 * v4 + 4 * g;
+                if (d < dh)
+                    store4_bf16(orow + d, accO[dt][4 * v4] * inv, accO[dt][4 * v4 + 1] * inv,
+                                accO[dt][4 * v4 + 2] * inv, accO[dt][4 * v4 + 3] * inv);
+            }
+        if (g == 0) lse[(int64_t)bh * T + q] = m + __logf(l);
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// backward pass 1: dQ and delta (wavefront owns 32 query rows)
+// ----------------------------------------------------------------------------------------
+template <int DHP>
+__global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+                                                        const bf16* __restrict__ dout, const float* __restrict__ lse,
+                                                        bf16* __restrict__ dqkv, float* __restrict__ delta,
+                                                        int T, int H, int dh) {
+    using C = AtCfg<DHP>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Vs = Ks + AT_ROWS * C::PITCH;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int g = lane >> 5;
+    const int bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int D = H * dh;
+    const int64_t ld = 3 * (int64_t)D;
+    const bf16* base = qkv + (int64_t)b * T * ld + h * dh;
+    const bf16* dob = dout + (int64_t)b * T * D + h * dh;
+    const bf16* ob = o + (int64_t)b * T * D + h * dh;
+    const int q0 = (blockIdx.x * nw + wave) * 32;
+    const int q = q0 + (lane & 31), qc = min(q, T - 1);
+    const float scale = rsqrtf((float)dh);
+
+    bf16x8_t bq[C::KS], bdo[C::KS];
+    load_owned<DHP>(base, ld, q0, T, dh, lane, bq);
+    load_owned<DHP>(dob, D, q0, T, dh, lane, bdo);
+    // delta_q = sum_d dO[q,d] * O[q,d]; the two half-wavefronts hold complementary feature slots
+    float dl = 0.f;
+    {
+        bf16x8_t bo[C::KS];
+        load_owned<DHP>(ob, D, q0, T, dh, lane, bo);
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dl += (float)bdo[ks][e] * (float)bo[ks][e];
+        dl += __shfl_xor(dl, 32, 64);
+    }
+    const float L = lse[(int64_t)bh * T + qc];
+    if (q < T && g == 0) delta[(int64_t)bh * T + q] = dl;
+
+    f32x16_t accQ[C::DT];
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accQ[dt][v] = 0.f;
+
+    for (int k0 = 0; k0 < T; k0 += AT_ROWS) {
+        __syncthreads();
+        load_tile<DHP>(Ks, base + D, ld, k0, T, dh);
+        load_tile<DHP>(Vs, base + 2 * D, ld, k0, T, dh);
+        __syncthreads();
+        const int nt = (T - k0 > 32) ? 2 : 1;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (t < nt) {
+                f32x16_t aS, aP;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { aS[v] = 0.f; aP[v] = 0.f; }
+                const uint16_t* kp = Ks + (t * 32 + (lane & 31)) * C::PITCH + 8 * g;
+                const uint16_t* vp = Vs + (t * 32 + (lane & 31)) * C::PITCH + 8 * g;
+#pragma unroll
+                for (int ks = 0; ks < C::KS; ++ks) {
+                    aS = mfma32(*reinterpret_cast<const bf16x8_t*>(kp + 16 * ks), bq[ks], aS);
+                    aP = mfma32(*reinterpret_cast<const bf16x8_t*>(vp + 16 * ks), bdo[ks], aP);
+                }
+                float ds[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const float p = (key < T) ? __expf(aS[v] * scale - L) : 0.f;
+                    ds[v] = p * (aP[v] - dl) * scale;
+                }
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const bf16x8_t dsb = pack8(&ds[8 * c]);
+#pragma unroll
+                    for (int dt = 0; dt < C::DT; ++dt) {
+                        const bf16x8_t a = tr_frag<4, 8>(Ks, C::PITCH, t * 32 + 16 * c, dt * 32, lane);
+                        accQ[dt] = mfma32(a, dsb, accQ[dt]);
+                    }
+                }
+            }
+        }
+    }
+    if (q < T) {
+        bf16* dq = dqkv + ((int64_t)b * T + q) * ld + h * dh;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int d = dt * 32 + 8 * v4 + 4 * g;
+                if (d < dh)
+                    store4_bf16(dq + d, accQ[dt][4 * v4], accQ[dt][4 * v4 + 1], accQ[dt][4 * v4 + 2], accQ[dt][4 * v4 + 3]);
+            }
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// backward pass 2: dK and dV (wavefront owns 32 key rows)
+// ----------------------------------------------------------------------------------------
+template <int DHP>
+__global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+                                                         const float* __restrict__ lse, const float* __restrict__ delta,
+                                                         bf16* __restrict__ dqkv, int T, int H, int dh) {
+    using C = AtCfg<DHP>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* Qs = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Os = Qs + AT_ROWS * C::PITCH;                       // dO tile
+    float* lse_s = reinterpret_cast<float*>(Os + AT_ROWS * C::PITCH);
+    float* del_s = lse_s + AT_ROWS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int g = lane >> 5;
+    const int bh = blockIdx.y, b = bh / H, h = bh % H;
+    const int D = H * dh;
+    const int64_t ld = 3 * (int64_t)D;
+    const bf16* base = qkv + (int64_t)b * T * ld + h * dh;
+    const bf16* dob = dout + (int64_t)b * T * D + h * dh;
+    const int j0 = (blockIdx.x * nw + wave) * 32;
+    const float scale = rsqrtf((float)dh);
+
+    bf16x8_t bk[C::KS], bv[C::KS];
+    load_owned<DHP>(base + D, ld, j0, T, dh, lane, bk);
+    load_owned<DHP>(base + 2 * D, ld, j0, T, dh, lane, bv);
+
+    f32x16_t accK[C::DT], accV[C::DT];
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { accK[dt][v] = 0.f; accV[dt][v] = 0.f; }
+
+    for (int i0 = 0; i0 < T; i0 += AT_ROWS) {
+        __syncthreads();
+        load_tile<DHP>(Qs, base, ld, i0, T, dh);
+        load_tile<DHP>(Os, dob, D, i0, T, dh);
+        for (int r = threadIdx.x; r < AT_ROWS; r += blockDim.x) {
+            const int i = i0 + r;
+            lse_s[r] = (i < T) ? lse[(int64_t)bh * T + i] : INFINITY;     // exp(. - inf) = 0 masks the row
+            del_s[r] = (i < T) ? delta[(int64_t)bh * T + i] : 0.f;
+        }
+        __syncthreads();
+        const int nt = (T - i0 > 32) ? 2 : 1;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (t < nt) {
+                f32x16_t aS, aP;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { aS[v] = 0.f; aP[v] = 0.f; }
+                const uint16_t* qp = Qs + (t * 32 + (lane & 31)) * C::PITCH + 8 * g;
+                const uint16_t* op = Os + (t * 32 + (lane & 31)) * C::PITCH + 8 * g;
+#pragma unroll
+                for (int ks = 0; ks < C::KS; ++ks) {
+                    aS = mfma32(*reinterpret_cast<const bf16x8_t*>(qp + 16 * ks), bk[ks], aS);
+                    aP = mfma32(*reinterpret_cast<const bf16x8_t*>(op + 16 * ks), bv[ks], aP);
+                }
+                // lane: key j0 + l%32; rows i = i0 + t*32 + 8*(v/4) + 4g + v%4
+                float p[16], ds[16];
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const int r = t * 32 + 8 * v4 + 4 * g;
+                    const float4 Lr = *reinterpret_cast<const float4*>(lse_s + r);
+                    const float4 Dr = *reinterpret_cast<const float4*>(del_s + r);
+                    const float Lv[4] = {Lr.x, Lr.y, Lr.z, Lr.w};
+                    const float Dv[4] = {Dr.x, Dr.y, Dr.z, Dr.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = 4 * v4 + e;
+                        p[v] = __expf(aS[v] * scale - Lv[e]);
+                        ds[v] = p[v] * (aP[v] - Dv[e]) * scale;
+                    }
+                }
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const bf16x8_t pb = pack8(&p[8 * c]);
+                    const bf16x8_t dsb = pack8(&ds[8 * c]);
+#pragma unroll
+                    for (int dt = 0; dt < C::DT; ++dt) {
+                        const bf16x8_t ao = tr_frag<4, 8>(Os, C::PITCH, t * 32 + 16 * c, dt * 32, lane);
+                        accV[dt] = mfma32(ao, pb, accV[dt]);
+                        const bf16x8_t aq = tr_frag<4, 8>(Qs, C::PITCH, t * 32 + 16 * c, dt * 32, lane);
+                        accK[dt] = mfma32(aq, dsb, accK[dt]);
+                    }
+                }
+            }
+        }
+    }
+    const int j = j0 + (lane & 31);
+    if (j < T) {
+        bf16* dk = dqkv + ((int64_t)b * T + j) * ld + D + h * dh;
+        bf16* dv = dk + D;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int d = dt * 32 + 8 * v4 + 4 * g;
+                if (d < dh) {
+                    store4_bf16(dk + d, accK[dt][4 * v4], accK[dt][4 * v4 + 1], accK[dt][4 * v4 + 2], accK[dt][4 * v4 + 3]);
+                    store4_bf16(dv + d, accV[dt][4 * v4], accV[dt][4 * v4 + 1], accV[dt][4 * v4 + 2], accV[dt][4 * v4 + 3]);
+                }
+            }
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// launchers
+// ----------------------------------------------------------------------------------------
+// Wavefronts per workgroup: split the ceil(T/32) row tiles evenly over as few workgroups as
+// 8 wavefronts each allow (T=197: 1 x 7, T=257: 2 x 5, T=512: 2 x 8).
+static void row_split(int T, int* nblk, int* nw) {
+    const int tiles = (T + 31) / 32;
+    *nblk = (tiles + 7) / 8;
+    *nw = (tiles + *nblk - 1) / *nblk;
+}
+
+template <int DHP>
+static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B, int T, int H, int dh) {
+    int nblk, nw;
+    row_split(T, &nblk, &nw);
+    const size_t shmem = (size_t)2 * AT_ROWS * AtCfg<DHP>::PITCH * sizeof(uint16_t);
+    hipLaunchKernelGGL((attn_fwd_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, lse, T, H, dh);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+template <int DHP>
+static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse, bf16* dqkv,
+                      float* delta, int B, int T, int H, int dh) {
+    int nblk, nw;
+    row_split(T, &nblk, &nw);
+    const size_t shmem = (size_t)2 * AT_ROWS * AtCfg<DHP>::PITCH * sizeof(uint16_t);
+    hipLaunchKernelGGL((attn_bwd_dq_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, dout, lse, dqkv,
+                       delta, T, H, dh);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem + 2 * AT_ROWS * sizeof(float),
+                       s, qkv, dout, lse, delta, dqkv, T, H, dh);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+static bool mfma_ok(const void* a, const void* b, const void* c, const void* d) {
+    return (((uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)d) & 15) == 0;
+}
+
+template <>
+int attention_forward<bf16>(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B, int T, int H, int dh) {
+    if ((dh & 7) || dh > 128 || !mfma_ok(qkv, o, nullptr, nullptr))
+        return attention_forward_simple<bf16>(s, qkv, o, lse, B, T, H, dh);
+    ProfScope ps(K_ATTN_FWD, s, 4.0 * B * H * (double)T * T * dh);
+    if (dh <= 32) return fwd_launch<32>(s, qkv, o, lse, B, T, H, dh);
+    if (dh <= 64) return fwd_launch<64>(s, qkv, o, lse, B, T, H, dh);
+    if (dh <= 96) return fwd_launch<96>(s, qkv, o, lse, B, T, H, dh);
+    return fwd_launch<128>(s, qkv, o, lse, B, T, H, dh);
+}
+template <>
+int attention_forward<float>(hipStream_t s, const float* qkv, float* o, float* lse, int B, int T, int H, int dh) {
+    return attention_forward_simple<float>(s, qkv, o, lse, B, T, H, dh);
+}
+
+template <>
+int attention_backward<bf16>(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse,
+                             bf16* dqkv, float* delta, int B, int T, int H, int dh) {
+    if ((dh & 7) || dh > 128 || !mfma_ok(qkv, o, dout, dqkv))
+        return attention_backward_simple<bf16>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+    ProfScope ps(K_ATTN_BWD, s, 8.0 * B * H * (double)T * T * dh);
+    if (dh <= 32) return bwd_launch<32>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+    if (dh <= 64) return bwd_launch<64>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+    if (dh <= 96) return bwd_launch<96>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+    return bwd_launch<128>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+}
+template <>
+int attention_backward<float>(hipStream_t s, const float* qkv, const float* o, const float* dout, const float* lse,
+                              float* dqkv, float* delta, int B, int T, int H, int dh) {
+    return attention_backward_simple<float>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+}
+
+}  // namespace rev

@@ -13,25 +13,9 @@
 // Register layout of the 32x32x16 instruction, per lane l of the wavefront:
 //   A operand: row l%32, k = 8*(l/32) .. +7;  B operand: column l%32, same k;
 //   D: column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for accumulator register v.
-#include "common.h"
+#include "mfma.h"
 
 namespace rev {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
-
-// Workgroups go round-robin over the 8 XCDs, each with its own L2: give every
-// XCD one contiguous run of tiles so that neighbouring tiles (which share an
-// operand panel) meet in the same L2.
-__device__ __forceinline__ int xcd_remap(int b, int nblk) {
-    const int per = nblk >> 3;
-    if (b >= per * 8) return b;
-    return (b & 7) * per + (b >> 3);
-}
 
 // ----------------------------------------------------------------------------------------
 // epilogues (compile-time kind); m, n are global indices, acc the float32 sum
@@ -204,27 +188,6 @@ constexpr int WG_BQ = 128;            // tile cols (k)
 constexpr int WG_BR = 64;             // tokens per step
 constexpr int WG_LDP = 128 + 32;      // LDS pitch in elements (320 B)
 
-// LDS transpose read: the 16 lanes of a group hand in 4x4 row chunks (4 rows r, 4
-// chunks of 4 columns) and lane j of the group receives column j of those rows,
-// i.e. 4 consecutive r for its own column.
-__device__ __forceinline__ s16x4_t lds_tr16(const uint16_t* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, p));
-}
-
-// fragment for rows/cols c0..c0+31 of the tile and the 16 tokens r0..r0+15
-__device__ __forceinline__ bf16x8_t tr_frag(const uint16_t* tile, int pitch, int r0, int c0, int lane) {
-    const int j = lane & 15, g = lane >> 4;
-    const int c = c0 + (g & 1) * 16 + 4 * (j & 3);
-    const int r = r0 + (g >> 1) * 8 + (j >> 2);
-    const uint16_t* p = tile + r * pitch + c;
-    s16x4_t lo = lds_tr16(p);
-    s16x4_t hi = lds_tr16(p + 4 * pitch);
-    union { struct { s16x4_t lo, hi; } s; bf16x8_t v; } u;
-    u.s.lo = lo;
-    u.s.hi = hi;
-    return u.v;
-}
-
 static int wgrad_splits(int M, int N, int K) {
     const int tiles = ((N + WG_BP - 1) / WG_BP) * ((K + WG_BQ - 1) / WG_BQ);
     int S = (512 + tiles - 1) / tiles;
@@ -301,9 +264,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const bf16* __restrict__ G, 
         for (int kk = 0; kk < WG_BR / 16; ++kk) {
             bf16x8_t a[2], b[2];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = tr_frag(Gt, WG_LDP, kk * 16, wp * 64 + i * 32, lane);
+            for (int i = 0; i < 2; ++i) a[i] = tr_frag<8, 4>(Gt, WG_LDP, kk * 16, wp * 64 + i * 32, lane);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = tr_frag(At, WG_LDP, kk * 16, wq * 64 + j * 32, lane);
+            for (int j = 0; j < 2; ++j) b[j] = tr_frag<8, 4>(At, WG_LDP, kk * 16, wq * 64 + j * 32, lane);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -359,22 +322,5 @@ int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, in
     if (S > 1) return reduce_rows(s, partial, S, (int64_t)N * K, (int64_t)N * K, dW);
     return REV_OK;
 }
-
-// ----------------------------------------------------------------------------------------
-// attention dispatch (plain kernels until the matrix-core versions take over)
-// ----------------------------------------------------------------------------------------
-template <typename TA>
-int attention_forward(hipStream_t s, const TA* qkv, TA* o, float* lse, int B, int T, int H, int dh) {
-    return attention_forward_simple<TA>(s, qkv, o, lse, B, T, H, dh);
-}
-template <typename TA>
-int attention_backward(hipStream_t s, const TA* qkv, const TA* o, const TA* dout, const float* lse,
-                       TA* dqkv, float* delta, int B, int T, int H, int dh) {
-    return attention_backward_simple<TA>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
-}
-template int attention_forward<float>(hipStream_t, const float*, float*, float*, int, int, int, int);
-template int attention_forward<bf16>(hipStream_t, const bf16*, bf16*, float*, int, int, int, int);
-template int attention_backward<float>(hipStream_t, const float*, const float*, const float*, const float*, float*, float*, int, int, int, int);
-template int attention_backward<bf16>(hipStream_t, const bf16*, const bf16*, const bf16*, const float*, bf16*, float*, int, int, int, int);
 
 }  // namespace rev

@@ -1,0 +1,58 @@
+// Matrix-core and LDS helpers shared by the bf16 GEMM and attention kernels (gfx950).
+//
+// v_mfma_f32_32x32x16_bf16, per lane l of the wavefront (g = l / 32):
+//   A operand: row l%32, contraction slots 8g .. 8g+7;  B operand: column l%32, same slots;
+//   D: column l%32, rows 8*(v/4) + 4g + v%4 for accumulator register v = 0..15.
+// The contraction slots may stand for any 16 indices as long as A and B agree.
+#pragma once
+#include "common.h"
+
+namespace rev {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+__device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// LDS transpose read (ds_read_b64_tr_b16): the 16 lanes of a group hand in a 4x4
+// arrangement of 8-byte chunks (lane 4e+q: row e, columns 4q..4q+3 of a 4x16 patch)
+// and lane j of the group receives column j of the patch: 4 consecutive rows.
+__device__ __forceinline__ s16x4_t lds_tr16(const uint16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, p));
+}
+
+// Operand fragment for 32 columns c0..c0+31 of a row-major LDS tile whose ROWS are
+// the contraction index.  Lane (l%32, g) receives rows  r0 + GS*g + {0..3}  and
+// r0 + GS*g + SEC + {0..3}  of column c0 + l%32.
+//   GS = 8, SEC = 4: slots are 16 consecutive rows r0..r0+15;
+//   GS = 4, SEC = 8: slots follow the accumulator row order {4g..4g+3, 8+4g..8+4g+3},
+//                    so a D tile converted in place can be the other operand.
+template <int GS, int SEC>
+__device__ __forceinline__ bf16x8_t tr_frag(const uint16_t* tile, int pitch, int r0, int c0, int lane) {
+    const int j = lane & 15, q = lane >> 4;
+    const int c = c0 + (q & 1) * 16 + 4 * (j & 3);
+    const int r = r0 + (q >> 1) * GS + (j >> 2);
+    const uint16_t* p = tile + r * pitch + c;
+    union { struct { s16x4_t lo, hi; } s; bf16x8_t v; } u;
+    u.s.lo = lds_tr16(p);
+    u.s.hi = lds_tr16(p + SEC * pitch);
+    return u.v;
+}
+
+// Workgroups go round-robin over the 8 XCDs, each with its own L2: give every
+// XCD one contiguous run of tiles so that neighbouring tiles (which share an
+// operand panel) meet in the same L2.
+__device__ __forceinline__ int xcd_remap(int b, int nblk) {
+    const int per = nblk >> 3;
+    if (b >= per * 8) return b;
+    return (b & 7) * per + (b >> 3);
+}
+
+}  // namespace rev
