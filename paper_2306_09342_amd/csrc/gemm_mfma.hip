@@ -165,12 +165,19 @@ static int launch_nt(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, i
     return REV_OK;
 }
 
+int gemm_nt_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                     int M, int N, int K, const Epi& epi);
+
 int gemm_nt_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
                  int M, int N, int K, const Epi& epi) {
     if ((lda & 7) || (ldb & 7) || (K & 7) || ((uintptr_t)A & 15) || ((uintptr_t)B & 15)) {
         return gemm_nt_bf16_simple(s, A, lda, B, ldb, M, N, K, epi);
     }
     ProfScope ps(K_GEMM_NT, s, 2.0 * M * N * K);
+    const uintptr_t ptrs = (uintptr_t)epi.out | (uintptr_t)epi.out2 | (uintptr_t)epi.outf | (uintptr_t)epi.bias |
+                           (uintptr_t)epi.res | (uintptr_t)epi.aux;
+    if (K % 64 == 0 && N % 4 == 0 && epi.ldo % 4 == 0 && (ptrs & 15) == 0)
+        return gemm_nt_bf16_dma(s, A, lda, B, ldb, M, N, K, epi);
     switch (epi.kind) {
 #define CASE(KIND) case KIND: return launch_nt<128, 128, 2, 2, KIND>(s, A, lda, B, ldb, M, N, K, epi);
         CASE(EPI_BIAS) CASE(EPI_BIAS_GELU) CASE(EPI_RESIDUAL) CASE(EPI_GELU_BWD) CASE(EPI_PLAIN) CASE(EPI_PLAIN_F32)

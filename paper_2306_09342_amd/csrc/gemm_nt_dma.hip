@@ -1,0 +1,269 @@
+// NT GEMM, pipelined flavour:  C[M,N] (+epilogue) = A[M,K] * B[N,K]^T  for K % 64 == 0.
+//
+// Operand tiles travel HBM -> LDS with the direct-to-LDS loads of gfx950
+// (global_load_lds_dwordx4): no staging registers, no LDS store instructions.
+// A ring of NS stages is kept in flight; a stage is consumed after
+// s_waitcnt vmcnt(.) (this wavefront's loads of the stage have landed) and one
+// workgroup barrier (everybody's have, and everybody is done reading the stage
+// that is about to be refilled).
+//
+// LDS tile layout: rows of 64 bf16 (128 B), dense.  A direct-to-LDS load drops the
+// 64 lanes' 16-byte pieces contiguously, so instead of padding the rows the
+// 16-byte chunk c of row r is kept at position c ^ ((r >> 1) & 7): each lane
+// simply fetches the global chunk that belongs at its LDS position.  Fragment
+// reads (16 rows x one chunk per quarter-wavefront) then hit 16 distinct bank
+// groups.
+//
+// The matrix-core product is taken as C^T = B * A^T (weights on the A port), so a
+// lane's accumulator quad holds 4 consecutive output columns; the tile goes
+// through LDS once and leaves in full contiguous rows with 16-byte accesses,
+// the epilogue (bias, GELU, GELU', residual) applied on the way out.
+#include "mfma.h"
+
+namespace rev {
+
+#define GLB_PTR(p) ((__attribute__((address_space(1))) const void*)(p))
+
+// s_waitcnt immediate for gfx9: vmcnt in bits [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]
+constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4); }
+
+// erf by the five-term rational-exponential formula (Abramowitz & Stegun 7.1.26,
+// |error| < 1.5e-7), sharing exp(-x^2/2) between GELU and its derivative.
+struct GeluParts { float cdf, pdf; };
+__device__ __forceinline__ GeluParts gelu_parts(float x) {
+    const float ax = fabsf(x);
+    const float e = __expf(-0.5f * x * x);                       // exp(-z^2), z = |x| / sqrt(2)
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * 0.70710678118654752f * ax);
+    float poly = 1.061405429f;
+    poly = poly * t - 1.453152027f;
+    poly = poly * t + 1.421413741f;
+    poly = poly * t - 0.284496736f;
+    poly = poly * t + 0.254829592f;
+    const float erfa = 1.0f - poly * t * e;                       // erf(z) for z >= 0
+    GeluParts r;
+    r.cdf = 0.5f * (1.0f + copysignf(erfa, x));
+    r.pdf = 0.39894228040143268f * e;
+    return r;
+}
+
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4_t ld_bf16x4(const void* p) {
+    const u32x2_t u = *reinterpret_cast<const u32x2_t*>(p);
+    f32x4_t r;
+    r[0] = __uint_as_float(u[0] << 16);
+    r[1] = __uint_as_float(u[0] & 0xFFFF0000u);
+    r[2] = __uint_as_float(u[1] << 16);
+    r[3] = __uint_as_float(u[1] & 0xFFFF0000u);
+    return r;
+}
+__device__ __forceinline__ void st_bf16x4(void* p, f32x4_t v) {
+    bf16x4_t b;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) b[e] = (__bf16)v[e];
+    *reinterpret_cast<bf16x4_t*>(p) = b;
+}
+
+// 4 consecutive output columns n..n+3 of row m
+template <int KIND>
+__device__ __forceinline__ void epi_store4(const Epi& e, int m, int n, f32x4_t acc) {
+    const int64_t idx = (int64_t)m * e.ldo + n;
+    if (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) {
+        const f32x4_t bv = ld_bf16x4(reinterpret_cast<const bf16*>(e.bias) + n);
+        acc += bv;
+    }
+    if (KIND == EPI_BIAS) {
+        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
+    } else if (KIND == EPI_BIAS_GELU) {
+        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
+        f32x4_t a;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a[k] = acc[k] * gelu_parts(acc[k]).cdf;
+        st_bf16x4(reinterpret_cast<bf16*>(e.out2) + idx, a);
+    } else if (KIND == EPI_RESIDUAL) {
+        const f32x4_t r = *reinterpret_cast<const f32x4_t*>(e.res + idx);
+        *reinterpret_cast<f32x4_t*>(e.outf + idx) = r + e.sign * acc;
+    } else if (KIND == EPI_GELU_BWD) {
+        const f32x4_t h = ld_bf16x4(reinterpret_cast<const bf16*>(e.aux) + idx);
+        f32x4_t o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const GeluParts g = gelu_parts(h[k]);
+            o[k] = acc[k] * (g.cdf + h[k] * g.pdf);
+        }
+        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, o);
+    } else if (KIND == EPI_PLAIN) {
+        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
+    } else {
+        *reinterpret_cast<f32x4_t*>(e.outf + idx) = acc;
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int NS, int KIND>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* __restrict__ A, int64_t lda,
+                                                                    const bf16* __restrict__ B, int64_t ldb,
+                                                                    int M, int N, int K, Epi epi) {
+    constexpr int NW = WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+    constexpr int IA = BM / 8, IB = BN / 8;              // wavefront-wide loads per stage
+    constexpr int LPW = (IA + IB) / NW;                  // ... per wavefront
+    static_assert(IA % NW == 0 && IB % NW == 0, "loads must split evenly over the wavefronts");
+    static_assert((NS - 2) * LPW < 64, "vmcnt range");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int g = lane >> 5;
+    const int tiles_n = (N + BN - 1) / BN;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+
+    // per-lane source pointers of this wavefront's loads (advance 64 elements per stage)
+    const bf16* src[LPW];
+    int dst[LPW];
+#pragma unroll
+    for (int t = 0; t < LPW; ++t) {
+        const int i = wave + NW * t;                     // load index within the stage: A first, then B
+        const bool isA = (NW * t) < IA;                  // uniform per t because IA % NW == 0
+        const int ii = isA ? i : i - IA;
+        const int row = ii * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        if (isA) {
+            src[t] = A + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8;
+            dst[t] = ii * 1024;
+        } else {
+            src[t] = B + (int64_t)min(n0 + row, N - 1) * ldb + chunk * 8;
+            dst[t] = A_BYTES + ii * 1024;
+        }
+    }
+    auto issue = [&](int kt, int stage) {
+#pragma unroll
+        for (int t = 0; t < LPW; ++t)
+            __builtin_amdgcn_global_load_lds(GLB_PTR(src[t] + (int64_t)kt * 64), LDS_PTR(void, smem + stage * STAGE + dst[t]),
+                                             16, 0, 0);
+    };
+
+    f32x16_t acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
+
+    const int nk = K / 64;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) issue(s, s);
+
+    // fragment addressing: row r of a tile region, chunk (2*kk + g) swizzled by (r >> 1) & 7
+    const int fr = lane & 31;
+    const int sw = (fr >> 1) & 7;
+    int koff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) koff[kk] = ((2 * kk + g) ^ sw) << 4;
+    const int a_row = (wm * TM * 32 + fr) * 128;
+    const int b_row = A_BYTES + (wn * TN * 32 + fr) * 128;
+
+    for (int kt = 0; kt < nk; ++kt) {
+        // loads of stage kt are older than the (NS-2) stages issued after them
+        if (kt + NS - 2 < nk) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * LPW));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+        __builtin_amdgcn_s_barrier();
+#if !defined(REV_EXP_NOLOAD)
+        if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
+#endif
+        const unsigned char* st = smem + (kt % NS) * STAGE;
+#if defined(REV_EXP_NOCOMPUTE)
+        if (kt >= 0) continue;
+#endif
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8_t a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * 128 + koff[kk]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * 128 + koff[kk]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[j][i] = mfma32(b[j], a[i], acc[j][i]);
+        }
+    }
+
+    // ---- epilogue through LDS: wavefront-private [TM*32 rows][TN*32 + 4] float32 ----
+    constexpr int CW = TN * 32, CP = CW + 4;
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+    __builtin_amdgcn_s_barrier();                         // every wavefront is done with the operand stages
+    float* ct = reinterpret_cast<float*>(smem) + wave * (TM * 32 * CP);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                f32x4_t v = {acc[j][i][4 * vq], acc[j][i][4 * vq + 1], acc[j][i][4 * vq + 2], acc[j][i][4 * vq + 3]};
+                *reinterpret_cast<f32x4_t*>(ct + (i * 32 + fr) * CP + j * 32 + 8 * vq + 4 * g) = v;
+            }
+    // the tile is private to the wavefront: its own LDS writes are ordered before its reads
+    constexpr int LPR = CW / 4;                           // lanes per row
+    constexpr int RPP = 64 / LPR;                         // rows per pass
+    const int c4 = lane % LPR, rr = lane / LPR;
+    const int n = n0 + wn * CW + 4 * c4;
+#pragma unroll
+    for (int p = 0; p < TM * 32 / RPP; ++p) {
+        const int row = p * RPP + rr;
+        const int m = m0 + wm * TM * 32 + row;
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ct + row * CP + 4 * c4);
+        if (m < M && n < N) epi_store4<KIND>(epi, m, n, v);
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int NS, int KIND>
+static int launch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
+                      const Epi& epi) {
+    constexpr int NW = WM * WN;
+    constexpr size_t stage_bytes = (size_t)NS * (BM + BN) * 128;
+    constexpr size_t epi_bytes = (size_t)NW * (BM / WM) * (BN / WN + 4) * 4;
+    constexpr size_t shmem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+    static bool attr_set = false;
+    auto kern = gemm_nt_dma_kernel<BM, BN, WM, WN, NS, KIND>;
+    if (!attr_set) {
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
+        attr_set = true;
+    }
+    const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * 64), shmem, s, A, lda, B, ldb, M, N, K, epi);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+int g_nt_variant = 1;   // tuning hook: tile shape of the pipelined NT GEMM
+
+template <int KIND>
+static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
+                        const Epi& epi) {
+    switch (g_nt_variant) {
+        case 1: return launch_dma<128, 128, 2, 2, 2, KIND>(s, A, lda, B, ldb, M, N, K, epi);
+        case 2: return launch_dma<256, 128, 4, 2, 3, KIND>(s, A, lda, B, ldb, M, N, K, epi);
+        case 3: return launch_dma<128, 128, 2, 2, 3, KIND>(s, A, lda, B, ldb, M, N, K, epi);
+        case 4: return launch_dma<256, 128, 4, 2, 2, KIND>(s, A, lda, B, ldb, M, N, K, epi);
+        default: return launch_dma<128, 128, 2, 2, 4, KIND>(s, A, lda, B, ldb, M, N, K, epi);
+    }
+}
+
+// Pipelined path; the caller has checked K % 64 == 0, N % 4 == 0 and 16-byte alignment of every row.
+int gemm_nt_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                     int M, int N, int K, const Epi& epi) {
+    switch (epi.kind) {
+#define CASE(KIND) case KIND: return dispatch_dma<KIND>(s, A, lda, B, ldb, M, N, K, epi);
+        CASE(EPI_BIAS) CASE(EPI_BIAS_GELU) CASE(EPI_RESIDUAL) CASE(EPI_GELU_BWD) CASE(EPI_PLAIN) CASE(EPI_PLAIN_F32)
+#undef CASE
+    }
+    set_error("gemm_nt_bf16: unknown epilogue");
+    return REV_EINVAL;
+}
+
+}  // namespace rev
