@@ -91,7 +91,12 @@ struct Epi {
     const void* aux;    // act-typed [M, ldo] (pre-activation for GELU backward)
     float sign;
     int64_t ldo;
+    float* colsum;      // EPI_GELU_BWD, matrix-core path: per-row-strip column sums of the output,
+                        // [gemm_colsum_rows(M)][N] float32 (nullable)
 };
+// 64-row strips of column-sum partials the matrix-core GEMM writes for M rows, and an upper bound for sizing
+int gemm_colsum_strips(int M);
+inline int gemm_colsum_strips_max(int M) { return ((M + 255) / 256) * 4; }
 
 // C[M,N] (+epilogue) = A[M,K] * B[N,K]^T.  A, B row-major with leading dims lda, ldb.
 // fp32 flavour: A, B float.  bf16 flavour: A, B bf16.
@@ -99,7 +104,13 @@ int gemm_nt_f32(hipStream_t s, const float* A, int64_t lda, const float* B, int6
                 int M, int N, int K, const Epi& epi);
 int gemm_nt_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
                  int M, int N, int K, const Epi& epi);
-// C[M,N] = A[M,K] * B[K,N]  (B row-major [K, ldb]); fp32 mode's dgrad.
+// C[M,N] = A[M,K] * B[K,N]  (B row-major [K, ldb]): the input-gradient form, weights as stored.
+int gemm_nn_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                 int M, int N, int K, const Epi& epi);
+// true when the pipelined matrix-core kernel (the one that honours Epi::colsum) takes this problem
+bool gemm_bf16_fast_path(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int N, int K, const Epi& epi);
+int gemm_nn_bf16_simple(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                        int M, int N, int K, const Epi& epi);
 int gemm_nn_f32(hipStream_t s, const float* A, int64_t lda, const float* B, int64_t ldb,
                 int M, int N, int K, const Epi& epi);
 // dW[N,K] (float32, ld = K) = G[M,N]^T * A[M,K]  -- reduction over the M tokens.
@@ -126,10 +137,11 @@ template <typename TA, typename TP>
 int ln_forward(hipStream_t s, const float* x, const TP* g, const TP* b, float eps,
                TA* y, float* stats, int M, int D);
 // out = r + LNbwd(dn; x, stats, g);  outb (nullable) = act-typed copy of out;
-// dg, db = column reductions (float32 [D]) via `partial` (>= ln_bwd_partial_elems floats)
+// dgb[0:D] = d gamma, dgb[D:2D] = d beta, dbias[D] (nullable) = column sums of out;
+// all three float32, summed in a fixed order via `partial` (>= ln_bwd_partial_elems floats)
 template <typename TA, typename TP>
 int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats, const TP* g,
-                const float* r, float* out, TA* outb, float* dg, float* db,
+                const float* r, float* out, TA* outb, float* dgb, float* dbias,
                 float* partial, int M, int D);
 int64_t ln_bwd_partial_elems(int M, int D);
 
@@ -140,6 +152,9 @@ int64_t colsum_partial_elems(int M, int N);
 
 // out[i] = sum_p partial[p * stride + i], p ascending
 int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out);
+// elements [0, split) go to out, [split, n) to out2 (nullable: dropped)
+int reduce_rows2(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out, float* out2,
+                 int64_t split);
 
 int convert_f32_to_bf16(hipStream_t s, const float* in, bf16* out, int64_t n);
 int copy_f32(hipStream_t s, const float* in, float* out, int64_t n);

@@ -117,8 +117,10 @@ template int ln_forward<bf16, bf16>(hipStream_t, const float*, const bf16*, cons
 // ---- LayerNorm backward + residual-gradient add -----------------------------------------
 // out = r + rstd * (dxh - mean(dxh) - xhat * mean(dxh * xhat)),  dxh = dn * g.
 // Each block walks LNB_ROWS consecutive rows (4 wavefronts, one row each at a
-// time); per-lane column accumulators for d gamma / d beta are folded across the
-// 4 wavefronts in LDS in wavefront order and written as one partial row per block.
+// time); per-lane column accumulators for d gamma, d beta and the column sums of
+// `out` itself (the bias gradient of the linear map that `out` is the cotangent
+// of) are folded across the 4 wavefronts in LDS in wavefront order and written
+// as one partial row [dgamma | dbeta | colsum(out)] per block.
 constexpr int LNB_ROWS = 32;
 
 template <typename TA, typename TP, int MAXJ>
@@ -127,14 +129,15 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
                                                      const float* __restrict__ r, float* __restrict__ out,
                                                      TA* __restrict__ outb, float* __restrict__ partial,
                                                      int M, int D) {
-    extern __shared__ float lds[];   // [2 * D]
+    extern __shared__ float lds[];   // [3 * D]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int nch = D >> 2;
-    f4 ag[MAXJ], ab[MAXJ], gg[MAXJ];
+    f4 ag[MAXJ], ab[MAXJ], ao[MAXJ], gg[MAXJ];
 #pragma unroll
     for (int j = 0; j < MAXJ; ++j) {
         ag[j] = {0.f, 0.f, 0.f, 0.f};
         ab[j] = {0.f, 0.f, 0.f, 0.f};
+        ao[j] = {0.f, 0.f, 0.f, 0.f};
         int c = lane + 64 * j;
         gg[j] = (c < nch) ? load4(g + 4 * c) : f4{0.f, 0.f, 0.f, 0.f};
     }
@@ -170,6 +173,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
                 o.y = rv.y + rstd * (dh[j].y - c1 - xh[j].y * c2);
                 o.z = rv.z + rstd * (dh[j].z - c1 - xh[j].z * c2);
                 o.w = rv.w + rstd * (dh[j].w - c1 - xh[j].w * c2);
+                ao[j].x += o.x; ao[j].y += o.y; ao[j].z += o.z; ao[j].w += o.w;
                 store4(out + base + 4 * c, o);
                 if (outb) store4(outb + base + 4 * c, o);
             }
@@ -184,25 +188,35 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
                 if (c < nch) {
                     float* pg = lds + 4 * c;
                     float* pb = lds + D + 4 * c;
+                    float* po = lds + 2 * D + 4 * c;
                     if (w == 0) {
                         pg[0] = ag[j].x; pg[1] = ag[j].y; pg[2] = ag[j].z; pg[3] = ag[j].w;
                         pb[0] = ab[j].x; pb[1] = ab[j].y; pb[2] = ab[j].z; pb[3] = ab[j].w;
+                        po[0] = ao[j].x; po[1] = ao[j].y; po[2] = ao[j].z; po[3] = ao[j].w;
                     } else {
                         pg[0] += ag[j].x; pg[1] += ag[j].y; pg[2] += ag[j].z; pg[3] += ag[j].w;
                         pb[0] += ab[j].x; pb[1] += ab[j].y; pb[2] += ab[j].z; pb[3] += ab[j].w;
+                        po[0] += ao[j].x; po[1] += ao[j].y; po[2] += ao[j].z; po[3] += ao[j].w;
                     }
                 }
             }
         }
         __syncthreads();
     }
-    float* prow = partial + (int64_t)blockIdx.x * 2 * D;
-    for (int i = threadIdx.x; i < 2 * D; i += 256) prow[i] = lds[i];
+    float* prow = partial + (int64_t)blockIdx.x * 3 * D;
+    for (int i = threadIdx.x; i < 3 * D; i += 256) prow[i] = lds[i];
 }
 
 // out[i] = sum over p (ascending) of partial[p * stride + i]; 4 elements per thread.
+// Elements at or beyond `split4` (in units of 4) go to out2 instead (nullable: dropped).
+__device__ __forceinline__ void reduce_store(float* out, float* out2, int64_t split4, int64_t i, float4 acc) {
+    if (i < split4) *reinterpret_cast<float4*>(out + 4 * i) = acc;
+    else if (out2) *reinterpret_cast<float4*>(out2 + 4 * (i - split4)) = acc;
+}
+
 __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ partial, int P,
-                                                          int64_t stride, int64_t n4, float* __restrict__ out) {
+                                                          int64_t stride, int64_t n4, float* __restrict__ out,
+                                                          float* __restrict__ out2, int64_t split4) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n4) return;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -210,13 +224,14 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
         float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * stride + 4 * i);
         acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
-    *reinterpret_cast<float4*>(out + 4 * i) = acc;
+    reduce_store(out, out2, split4, i, acc);
 }
 
 // Same sum for many partial rows: 16 row-lanes per column group walk the rows
 // p = lane, lane+16, ... and are folded in lane order through LDS.
 __global__ __launch_bounds__(256) void reduce_rows_wide_kernel(const float* __restrict__ partial, int P,
-                                                               int64_t stride, int64_t n4, float* __restrict__ out) {
+                                                               int64_t stride, int64_t n4, float* __restrict__ out,
+                                                               float* __restrict__ out2, int64_t split4) {
     __shared__ float4 sh[256];
     const int cg = threadIdx.x & 15, pl = threadIdx.x >> 4;
     const int64_t i = (int64_t)blockIdx.x * 16 + cg;
@@ -234,50 +249,63 @@ __global__ __launch_bounds__(256) void reduce_rows_wide_kernel(const float* __re
             float4 v = sh[q * 16 + cg];
             acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
         }
-        *reinterpret_cast<float4*>(out + 4 * i) = acc;
+        reduce_store(out, out2, split4, i, acc);
     }
 }
 
 int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out) {
-    if (n % 4 != 0) { set_error("reduce_rows: length must be a multiple of 4"); return REV_EINVAL; }
+    return reduce_rows2(s, partial, P, stride, n, out, nullptr, n);
+}
+
+// Elements [0, split) of the sum go to out, elements [split, n) to out2 (dropped if out2 is null).
+int reduce_rows2(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out, float* out2,
+                 int64_t split) {
+    if (n % 4 != 0 || split % 4 != 0) { set_error("reduce_rows: lengths must be multiples of 4"); return REV_EINVAL; }
+    const int64_t split4 = split / 4;
     ProfScope ps(K_REDUCE, s, (double)(P + 1) * n * 4);
     int64_t n4 = n / 4;
     if (P > 32) {
         hipLaunchKernelGGL(reduce_rows_wide_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, s, partial, P,
-                           stride, n4, out);
+                           stride, n4, out, out2, split4);
     } else {
         hipLaunchKernelGGL(reduce_rows_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, partial, P,
-                           stride, n4, out);
+                           stride, n4, out, out2, split4);
     }
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
 
 int64_t ln_bwd_partial_elems(int M, int D) {
-    return (int64_t)((M + LNB_ROWS - 1) / LNB_ROWS) * 2 * D;
+    return (int64_t)((M + LNB_ROWS - 1) / LNB_ROWS) * 3 * D;
 }
 
 template <typename TA, typename TP>
 int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats, const TP* g,
-                const float* r, float* out, TA* outb, float* dg, float* db,
+                const float* r, float* out, TA* outb, float* dgb, float* dbias,
                 float* partial, int M, int D) {
     const int nblk = (M + LNB_ROWS - 1) / LNB_ROWS;
     {
         ProfScope ps(K_LN_BWD, s, (double)M * D * (sizeof(TA) + 4 + 4 + 4 + (outb ? sizeof(TA) : 0)));
         dim3 grid(nblk), block(256);
-        size_t shmem = (size_t)2 * D * sizeof(float);
+        size_t shmem = (size_t)3 * D * sizeof(float);
         switch (pick_maxj(D)) {
-#define CASE(J) case J: hipLaunchKernelGGL((ln_bwd_kernel<TA, TP, J>), grid, block, shmem, s, dn, x, stats, g, r, out, outb, partial, M, D); break;
+#define CASE(J) case J: {                                                                                            \
+            auto kern = ln_bwd_kernel<TA, TP, J>;                                                                       \
+            static bool attr_set = false;                                                                               \
+            if (!attr_set) {                                                                                            \
+                REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 64 * J * 16)); \
+                attr_set = true;                                                                                        \
+            }                                                                                                           \
+            hipLaunchKernelGGL(kern, grid, block, shmem, s, dn, x, stats, g, r, out, outb, partial, M, D);          \
+        } break;
             CASE(2) CASE(4) CASE(8) CASE(16) CASE(32)
 #undef CASE
             default: set_error("ln_backward: d_model too large"); return REV_EINVAL;
         }
         REV_HIP(hipGetLastError());
     }
-    // partial rows are [dgamma(D) | dbeta(D)]; dg and db are separate outputs
-    int rc = reduce_rows(s, partial, nblk, 2 * (int64_t)D, D, dg);
-    if (rc) return rc;
-    return reduce_rows(s, partial + D, nblk, 2 * (int64_t)D, D, db);
+    // partial rows are [dgamma(D) | dbeta(D) | colsum(out)(D)]; gamma and beta gradients are adjacent in dgb
+    return reduce_rows2(s, partial, nblk, 3 * (int64_t)D, 3 * (int64_t)D, dgb, dbias, 2 * (int64_t)D);
 }
 template int ln_backward<float, float>(hipStream_t, const float*, const float*, const float*, const float*, const float*, float*, float*, float*, float*, float*, int, int);
 template int ln_backward<bf16, bf16>(hipStream_t, const bf16*, const float*, const float*, const bf16*, const float*, float*, bf16*, float*, float*, float*, int, int);

@@ -165,8 +165,22 @@ static int launch_nt(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, i
     return REV_OK;
 }
 
-int gemm_nt_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
-                     int M, int N, int K, const Epi& epi);
+int gemm_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                  int M, int N, int K, const Epi& epi, bool b_kmajor);
+
+bool gemm_bf16_fast_path(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int N, int K, const Epi& epi) {
+    const uintptr_t ptrs = (uintptr_t)A | (uintptr_t)B | (uintptr_t)epi.out | (uintptr_t)epi.out2 | (uintptr_t)epi.outf |
+                           (uintptr_t)epi.bias | (uintptr_t)epi.res | (uintptr_t)epi.aux;
+    return K % 64 == 0 && N % 8 == 0 && (lda & 7) == 0 && (ldb & 7) == 0 && epi.ldo % 4 == 0 && (ptrs & 15) == 0;
+}
+
+// C[M,N] = A[M,K] * B[K,N]   (B row-major [K, ldb]): the input-gradient form, weights as stored
+int gemm_nn_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                 int M, int N, int K, const Epi& epi) {
+    if (!gemm_bf16_fast_path(A, lda, B, ldb, N, K, epi)) return gemm_nn_bf16_simple(s, A, lda, B, ldb, M, N, K, epi);
+    ProfScope ps(K_GEMM_NT, s, 2.0 * M * N * K);
+    return gemm_bf16_dma(s, A, lda, B, ldb, M, N, K, epi, true);
+}
 
 int gemm_nt_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
                  int M, int N, int K, const Epi& epi) {
@@ -174,10 +188,7 @@ int gemm_nt_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64
         return gemm_nt_bf16_simple(s, A, lda, B, ldb, M, N, K, epi);
     }
     ProfScope ps(K_GEMM_NT, s, 2.0 * M * N * K);
-    const uintptr_t ptrs = (uintptr_t)epi.out | (uintptr_t)epi.out2 | (uintptr_t)epi.outf | (uintptr_t)epi.bias |
-                           (uintptr_t)epi.res | (uintptr_t)epi.aux;
-    if (K % 64 == 0 && N % 4 == 0 && epi.ldo % 4 == 0 && (ptrs & 15) == 0)
-        return gemm_nt_bf16_dma(s, A, lda, B, ldb, M, N, K, epi);
+    if (gemm_bf16_fast_path(A, lda, B, ldb, N, K, epi)) return gemm_bf16_dma(s, A, lda, B, ldb, M, N, K, epi, false);
     switch (epi.kind) {
 #define CASE(KIND) case KIND: return launch_nt<128, 128, 2, 2, KIND>(s, A, lda, B, ldb, M, N, K, epi);
         CASE(EPI_BIAS) CASE(EPI_BIAS_GELU) CASE(EPI_RESIDUAL) CASE(EPI_GELU_BWD) CASE(EPI_PLAIN) CASE(EPI_PLAIN_F32)
@@ -195,9 +206,11 @@ constexpr int WG_BQ = 128;            // tile cols (k)
 constexpr int WG_BR = 64;             // tokens per step
 constexpr int WG_LDP = 128 + 32;      // LDS pitch in elements (320 B)
 
+// The token reduction is cut into S ranges so that tiles * S fills, but does not exceed, the
+// workgroup slots of the chip (256 CUs x 2 resident workgroups): one full round, no ragged second one.
 static int wgrad_splits(int M, int N, int K) {
     const int tiles = ((N + WG_BP - 1) / WG_BP) * ((K + WG_BQ - 1) / WG_BQ);
-    int S = (512 + tiles - 1) / tiles;
+    int S = 512 / tiles;
     const int steps = (M + WG_BR - 1) / WG_BR;
     if (S > steps) S = steps;
     if (S > 16) S = 16;
@@ -301,6 +314,10 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const bf16* __restrict__ G, 
     }
 }
 
+int launch_wgrad_dma(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,
+                     int S, int sps, float* out);
+int g_wg_variant = 1;   // tuning hook: 0 = register-staged kernel, 1 = direct-to-LDS kernel
+
 int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
                     int M, int N, int K, float* dW, float* partial, int64_t partial_elems) {
     if ((ldg & 7) || (lda & 7) || (N & 7) || (K & 7) || ((uintptr_t)G & 15) || ((uintptr_t)A & 15)) {
@@ -320,7 +337,11 @@ int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, in
         REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
         attr_set = true;
     }
-    {
+    if (g_wg_variant == 1) {
+        ProfScope ps(K_GEMM_WGRAD, s, 2.0 * M * N * K);
+        int rc = launch_wgrad_dma(s, G, ldg, A, lda, M, N, K, S, sps, S > 1 ? partial : dW);
+        if (rc) return rc;
+    } else {
         ProfScope ps(K_GEMM_WGRAD, s, 2.0 * M * N * K);
         hipLaunchKernelGGL(wgrad_kernel, dim3(tiles * S), dim3(256), shmem, s, G, ldg, A, lda, M, N, K, sps,
                            S > 1 ? partial : dW, (int64_t)N * K);

@@ -22,11 +22,6 @@
 
 namespace rev {
 
-#define GLB_PTR(p) ((__attribute__((address_space(1))) const void*)(p))
-
-// s_waitcnt immediate for gfx9: vmcnt in bits [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8]
-constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4); }
-
 // erf by the five-term rational-exponential formula (Abramowitz & Stegun 7.1.26,
 // |error| < 1.5e-7), sharing exp(-x^2/2) between GELU and its derivative.
 struct GeluParts { float cdf, pdf; };
@@ -66,8 +61,9 @@ __device__ __forceinline__ void st_bf16x4(void* p, f32x4_t v) {
 }
 
 // 4 consecutive output columns n..n+3 of row m
+// (returns the float32 values behind the stored output, for the fused column sums)
 template <int KIND>
-__device__ __forceinline__ void epi_store4(const Epi& e, int m, int n, f32x4_t acc) {
+__device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_t acc) {
     const int64_t idx = (int64_t)m * e.ldo + n;
     if (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) {
         const f32x4_t bv = ld_bf16x4(reinterpret_cast<const bf16*>(e.bias) + n);
@@ -93,22 +89,31 @@ __device__ __forceinline__ void epi_store4(const Epi& e, int m, int n, f32x4_t a
             o[k] = acc[k] * (g.cdf + h[k] * g.pdf);
         }
         st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, o);
+        return o;
     } else if (KIND == EPI_PLAIN) {
         st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
     } else {
         *reinterpret_cast<f32x4_t*>(e.outf + idx) = acc;
     }
+    return acc;
 }
 
-template <int BM, int BN, int WM, int WN, int NS, int KIND>
+template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                     const bf16* __restrict__ B, int64_t ldb,
                                                                     int M, int N, int K, Epi epi) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-    constexpr int IA = BM / 8, IB = BN / 8;              // wavefront-wide loads per stage
+    constexpr int ROWB = BK * 2;                         // bytes per tile row
+    constexpr int CPR = BK / 8;                          // 16-byte chunks per row (8 or 4)
+    constexpr int RPI = 64 / CPR;                        // rows covered by one wavefront-wide load
+    // B is either [N, K] (rows contraction-contiguous, like A) or, with BKM, [K, N]: then its tile
+    // is BK rows of BN columns, kept as it lies in memory and read with the LDS transpose read
+    static_assert(!BKM || BN == 128, "K-major B tiles have 256-byte rows");
+    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int IA = BM / RPI, IB = B_BYTES / 1024;    // wavefront-wide loads per stage
     constexpr int LPW = (IA + IB) / NW;                  // ... per wavefront
+    static_assert(BK == 64 || BK == 32, "BK");
     static_assert(IA % NW == 0 && IB % NW == 0, "loads must split evenly over the wavefronts");
     static_assert((NS - 2) * LPW < 64, "vmcnt range");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -120,7 +125,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
-    // per-lane source pointers of this wavefront's loads (advance 64 elements per stage)
+    // chunk c of row r is kept at position c ^ swz(r): 16 consecutive rows x one chunk -> 16 distinct bank groups
+    auto swz = [](int r) { return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
+
+    // per-lane source pointers of this wavefront's loads (advance BK elements per stage)
     const bf16* src[LPW];
     int dst[LPW];
 #pragma unroll
@@ -128,21 +136,31 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         const int i = wave + NW * t;                     // load index within the stage: A first, then B
         const bool isA = (NW * t) < IA;                  // uniform per t because IA % NW == 0
         const int ii = isA ? i : i - IA;
-        const int row = ii * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        const int row = ii * RPI + lane / CPR;
+        const int chunk = (lane % CPR) ^ swz(row);
         if (isA) {
             src[t] = A + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8;
             dst[t] = ii * 1024;
-        } else {
+        } else if (!BKM) {
             src[t] = B + (int64_t)min(n0 + row, N - 1) * ldb + chunk * 8;
+            dst[t] = A_BYTES + ii * 1024;
+        } else {
+            // 4 contraction rows of 16 chunks per load; chunk c of row r at position c ^ (4 * (r & 3))
+            const int krow = ii * 4 + (lane >> 4);
+            const int col = n0 + (((lane & 15) ^ (4 * (krow & 3))) * 8);
+            src[t] = (col < N) ? B + (int64_t)krow * ldb + col : nullptr;    // null: columns beyond N read zeros
             dst[t] = A_BYTES + ii * 1024;
         }
     }
+    const int64_t bstep = BKM ? (int64_t)BK * ldb : (int64_t)BK;       // B advance per stage
+    const bf16* zero = reinterpret_cast<const bf16*>(g_zero_chunk);
     auto issue = [&](int kt, int stage) {
 #pragma unroll
-        for (int t = 0; t < LPW; ++t)
-            __builtin_amdgcn_global_load_lds(GLB_PTR(src[t] + (int64_t)kt * 64), LDS_PTR(void, smem + stage * STAGE + dst[t]),
-                                             16, 0, 0);
+        for (int t = 0; t < LPW; ++t) {
+            const bool isA = (NW * t) < IA;
+            const bf16* p = isA ? src[t] + (int64_t)kt * BK : (src[t] ? src[t] + kt * bstep : zero);
+            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(void, smem + stage * STAGE + dst[t]), 16, 0, 0);
+        }
     };
 
     f32x16_t acc[TN][TM];
@@ -153,19 +171,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0.f;
 
-    const int nk = K / 64;
+    const int nk = K / BK;
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (s < nk) issue(s, s);
 
-    // fragment addressing: row r of a tile region, chunk (2*kk + g) swizzled by (r >> 1) & 7
+    // fragment addressing: row r of a tile region, chunk (2*kk + g) swizzled
     const int fr = lane & 31;
-    const int sw = (fr >> 1) & 7;
-    int koff[4];
+    int koff[BK / 16];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) koff[kk] = ((2 * kk + g) ^ sw) << 4;
-    const int a_row = (wm * TM * 32 + fr) * 128;
-    const int b_row = A_BYTES + (wn * TN * 32 + fr) * 128;
+    for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = ((2 * kk + g) ^ swz(fr)) << 4;
+    const int a_row = (wm * TM * 32 + fr) * ROWB;
+    const int b_row = A_BYTES + (wn * TN * 32 + fr) * ROWB;
 
     for (int kt = 0; kt < nk; ++kt) {
         // loads of stage kt are older than the (NS-2) stages issued after them
@@ -180,12 +197,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         if (kt >= 0) continue;
 #endif
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8_t a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * 128 + koff[kk]);
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * ROWB + koff[kk]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * 128 + koff[kk]);
+            for (int j = 0; j < TN; ++j) {
+                if (BKM) b[j] = tr_frag_swz(st + A_BYTES, kk * 16, wn * TN * 32 + j * 32, lane);
+                else b[j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * ROWB + koff[kk]);
+            }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -193,43 +213,60 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         }
     }
 
-    // ---- epilogue through LDS: wavefront-private [TM*32 rows][TN*32 + 4] float32 ----
+    // ---- epilogue through LDS, 32 rows at a time: wavefront-private [32][TN*32 + 4] float32 ----
     constexpr int CW = TN * 32, CP = CW + 4;
+    constexpr int LPR = CW / 4;                           // lanes per row
+    constexpr int RPP = 64 / LPR;                         // rows per pass
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
     __builtin_amdgcn_s_barrier();                         // every wavefront is done with the operand stages
-    float* ct = reinterpret_cast<float*>(smem) + wave * (TM * 32 * CP);
+    float* ct = reinterpret_cast<float*>(smem) + wave * (32 * CP);
+    const int c4 = lane % LPR, rr = lane / LPR;
+    const int n = n0 + wn * CW + 4 * c4;
+    f32x4_t csum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
                 f32x4_t v = {acc[j][i][4 * vq], acc[j][i][4 * vq + 1], acc[j][i][4 * vq + 2], acc[j][i][4 * vq + 3]};
-                *reinterpret_cast<f32x4_t*>(ct + (i * 32 + fr) * CP + j * 32 + 8 * vq + 4 * g) = v;
+                *reinterpret_cast<f32x4_t*>(ct + fr * CP + j * 32 + 8 * vq + 4 * g) = v;
             }
-    // the tile is private to the wavefront: its own LDS writes are ordered before its reads
-    constexpr int LPR = CW / 4;                           // lanes per row
-    constexpr int RPP = 64 / LPR;                         // rows per pass
-    const int c4 = lane % LPR, rr = lane / LPR;
-    const int n = n0 + wn * CW + 4 * c4;
+        // the region is private to the wavefront and LDS operations of a wavefront complete in order
 #pragma unroll
-    for (int p = 0; p < TM * 32 / RPP; ++p) {
-        const int row = p * RPP + rr;
-        const int m = m0 + wm * TM * 32 + row;
-        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ct + row * CP + 4 * c4);
-        if (m < M && n < N) epi_store4<KIND>(epi, m, n, v);
+        for (int p = 0; p < 32 / RPP; ++p) {
+            const int row = p * RPP + rr;
+            const int m = m0 + wm * TM * 32 + i * 32 + row;
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ct + row * CP + 4 * c4);
+            if (m < M && n < N) {
+                const f32x4_t o = epi_store4<KIND>(epi, m, n, v);
+                if (KIND == EPI_GELU_BWD) csum += o;
+            }
+        }
+    }
+    // fused bias gradient: column sums of this wavefront's 64-row strip, lanes folded in a fixed order
+    if (KIND == EPI_GELU_BWD && epi.colsum != nullptr) {
+        static_assert(KIND != EPI_GELU_BWD || TM * 32 == 64, "column-sum strips are 64 rows");
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) csum[k] += __shfl_xor(csum[k], off, 64);
+        if (rr == 0 && n < N) {
+            const int strip = (m0 + wm * TM * 32) >> 6;
+            *reinterpret_cast<f32x4_t*>(epi.colsum + (int64_t)strip * N + n) = csum;
+        }
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NS, int KIND>
+template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 static int launch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                       const Epi& epi) {
     constexpr int NW = WM * WN;
-    constexpr size_t stage_bytes = (size_t)NS * (BM + BN) * 128;
-    constexpr size_t epi_bytes = (size_t)NW * (BM / WM) * (BN / WN + 4) * 4;
+    constexpr size_t stage_bytes = (size_t)NS * (BM + BN) * BK * 2;
+    constexpr size_t epi_bytes = (size_t)NW * 32 * (BN / WN + 4) * 4;
     constexpr size_t shmem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static bool attr_set = false;
-    auto kern = gemm_nt_dma_kernel<BM, BN, WM, WN, NS, KIND>;
+    auto kern = gemm_nt_dma_kernel<BM, BN, WM, WN, BK, NS, KIND, BKM>;
     if (!attr_set) {
         REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
         attr_set = true;
@@ -242,27 +279,33 @@ static int launch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, 
 
 int g_nt_variant = 1;   // tuning hook: tile shape of the pipelined NT GEMM
 
-template <int KIND>
+// number of 64-row strips whose column sums the EPI_GELU_BWD epilogue writes (whole tiles, so every
+// strip of every launched workgroup is written, those past M with zeros)
+int gemm_colsum_strips(int M) {
+    const int BM = (g_nt_variant == 2) ? 256 : 128;
+    return ((M + BM - 1) / BM) * (BM / 64);
+}
+
+template <int KIND, bool BKM>
 static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                         const Epi& epi) {
     switch (g_nt_variant) {
-        case 1: return launch_dma<128, 128, 2, 2, 2, KIND>(s, A, lda, B, ldb, M, N, K, epi);
-        case 2: return launch_dma<256, 128, 4, 2, 3, KIND>(s, A, lda, B, ldb, M, N, K, epi);
-        case 3: return launch_dma<128, 128, 2, 2, 3, KIND>(s, A, lda, B, ldb, M, N, K, epi);
-        case 4: return launch_dma<256, 128, 4, 2, 2, KIND>(s, A, lda, B, ldb, M, N, K, epi);
-        default: return launch_dma<128, 128, 2, 2, 4, KIND>(s, A, lda, B, ldb, M, N, K, epi);
+        case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+        default: return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
     }
 }
 
-// Pipelined path; the caller has checked K % 64 == 0, N % 4 == 0 and 16-byte alignment of every row.
-int gemm_nt_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
-                     int M, int N, int K, const Epi& epi) {
+// Pipelined path; the caller has checked K % 64 == 0, N % 8 == 0 and 16-byte alignment of every row.
+// b_kmajor = false: B is [N, K];  true: B is [K, N] (C = A * B).
+int gemm_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                  int M, int N, int K, const Epi& epi, bool b_kmajor) {
     switch (epi.kind) {
-#define CASE(KIND) case KIND: return dispatch_dma<KIND>(s, A, lda, B, ldb, M, N, K, epi);
+#define CASE(KIND) case KIND: return b_kmajor ? dispatch_dma<KIND, true>(s, A, lda, B, ldb, M, N, K, epi) \
+                                              : dispatch_dma<KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
         CASE(EPI_BIAS) CASE(EPI_BIAS_GELU) CASE(EPI_RESIDUAL) CASE(EPI_GELU_BWD) CASE(EPI_PLAIN) CASE(EPI_PLAIN_F32)
 #undef CASE
     }
-    set_error("gemm_nt_bf16: unknown epilogue");
+    set_error("gemm_bf16: unknown epilogue");
     return REV_EINVAL;
 }
 

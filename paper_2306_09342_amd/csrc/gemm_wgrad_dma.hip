@@ -1,0 +1,137 @@
+// Weight gradient, pipelined flavour:  dW[N,K] = sum over tokens m of G[m,n] * A[m,k].
+//
+// Both operands have the reduction index (the token) as their slow index.  Their
+// tiles -- 64 tokens x 128 columns -- go HBM -> LDS with direct-to-LDS loads in
+// the layout they have in memory, and the matrix-core fragments (8 consecutive
+// tokens of one column per lane) are gathered with the LDS transpose read, so
+// nothing is transposed in memory or in registers.
+//
+// LDS tile: rows of 128 bf16 (256 B), dense; the 16-byte chunk c of token row r
+// sits at position c ^ (4 * (r & 3)).  One transpose read touches 4 consecutive
+// token rows x 64 bytes per 32 lanes; the swizzle spreads those 4 rows over
+// the 4 quarters of the bank space.
+//
+// Tokens beyond M and columns beyond N / K are fetched from a block of zeros.
+#include "mfma.h"
+
+namespace rev {
+
+constexpr int WD_BP = 128, WD_BQ = 128, WD_BR = 64;
+constexpr int WD_TILE = WD_BR * 256;            // bytes of one operand tile
+constexpr int WD_STAGE = 2 * WD_TILE;
+
+template <int NS>
+__global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__ G, int64_t ldg,
+                                                        const bf16* __restrict__ A, int64_t lda,
+                                                        int M, int N, int K, int steps_per_split,
+                                                        float* __restrict__ out, int64_t split_stride) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wp = wave >> 1, wq = wave & 1;                       // 2 x 2 wavefronts, 64 x 64 each
+    const int tiles_q = (K + WD_BQ - 1) / WD_BQ;
+    const int tiles = ((N + WD_BP - 1) / WD_BP) * tiles_q;
+    const int split = blockIdx.x / tiles;
+    const int tile = xcd_remap(blockIdx.x % tiles, tiles);
+    const int p0 = (tile / tiles_q) * WD_BP, q0 = (tile % tiles_q) * WD_BQ;
+    const int total_steps = (M + WD_BR - 1) / WD_BR;
+    const int step0 = split * steps_per_split;
+    const int nsteps = max(0, min(steps_per_split, total_steps - step0));
+
+    // Each operand tile is 16 wavefront-wide loads of 4 token rows; wavefront w issues loads
+    // w, w+4, w+8, w+12 of G and the same of A.  Lane l: row 4*i + l/16, LDS position l%16.
+    constexpr int LPW = 8;
+    int rowl[4], chunk[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int i = wave + 4 * t;
+        rowl[t] = 4 * i + (lane >> 4);
+        chunk[t] = (lane & 15) ^ (4 * (rowl[t] & 3));
+    }
+    const bf16* zero = reinterpret_cast<const bf16*>(g_zero_chunk);
+    auto issue = [&](int st, int stage) {
+        const int mbase = (step0 + st) * WD_BR;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int m = mbase + rowl[t];
+            const int gp = p0 + chunk[t] * 8, gq = q0 + chunk[t] * 8;
+            const bf16* sg = (m < M && gp < N) ? G + (int64_t)m * ldg + gp : zero;
+            const bf16* sa = (m < M && gq < K) ? A + (int64_t)m * lda + gq : zero;
+            const int i = wave + 4 * t;
+            __builtin_amdgcn_global_load_lds(GLB_PTR(sg), LDS_PTR(void, smem + stage * WD_STAGE + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(GLB_PTR(sa), LDS_PTR(void, smem + stage * WD_STAGE + WD_TILE + i * 1024), 16, 0, 0);
+        }
+    };
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nsteps) issue(s, s);
+
+    for (int st = 0; st < nsteps; ++st) {
+        if (st + NS - 2 < nsteps) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * LPW));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+        __builtin_amdgcn_s_barrier();
+        if (st + NS - 1 < nsteps) issue(st + NS - 1, (st + NS - 1) % NS);
+        const unsigned char* Gt = smem + (st % NS) * WD_STAGE;
+        const unsigned char* At = Gt + WD_TILE;
+#pragma unroll
+        for (int kk = 0; kk < WD_BR / 16; ++kk) {
+            bf16x8_t a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = tr_frag_swz(Gt, kk * 16, wp * 64 + i * 32, lane);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = tr_frag_swz(At, kk * 16, wq * 64 + j * 32, lane);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
+        }
+    }
+
+    float* o = out + (int64_t)split * split_stride;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int q = q0 + wq * 64 + j * 32 + (lane & 31);
+        if (q >= K) continue;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int pb = p0 + wp * 64 + i * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int p = pb + 8 * (v >> 2) + (v & 3);
+                if (p < N) o[(int64_t)p * K + q] = acc[i][j][v];
+            }
+        }
+    }
+}
+
+int g_wg_stages = 2;   // tuning hook
+
+int launch_wgrad_dma(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,
+                     int S, int sps, float* out) {
+    const int tiles = ((N + WD_BP - 1) / WD_BP) * ((K + WD_BQ - 1) / WD_BQ);
+    static bool attr_set = false;
+    if (!attr_set) {
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_dma_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WD_STAGE));
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_dma_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * WD_STAGE));
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_dma_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * WD_STAGE));
+        attr_set = true;
+    }
+    if (g_wg_stages == 3)
+        hipLaunchKernelGGL(wgrad_dma_kernel<3>, dim3(tiles * S), dim3(256), 3 * WD_STAGE, s, G, ldg, A, lda, M, N, K, sps, out, (int64_t)N * K);
+    else if (g_wg_stages == 4)
+        hipLaunchKernelGGL(wgrad_dma_kernel<4>, dim3(tiles * S), dim3(256), 4 * WD_STAGE, s, G, ldg, A, lda, M, N, K, sps, out, (int64_t)N * K);
+    else
+        hipLaunchKernelGGL(wgrad_dma_kernel<2>, dim3(tiles * S), dim3(256), 2 * WD_STAGE, s, G, ldg, A, lda, M, N, K, sps, out, (int64_t)N * K);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
+}
+
+}  // namespace rev

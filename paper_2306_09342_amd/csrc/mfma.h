@@ -46,6 +46,29 @@ __device__ __forceinline__ bf16x8_t tr_frag(const uint16_t* tile, int pitch, int
     return u.v;
 }
 
+// Same fragment from a DENSE tile with 256-byte rows (128 bf16) whose 16-byte chunk c of row r
+// sits at position c ^ (4 * (r & 3)) -- the layout a direct-to-LDS load can produce.  One transpose
+// read touches 4 consecutive rows x 64 bytes per 32 lanes; the swizzle spreads the 4 rows over the
+// 4 quarters of the bank space.  Slots: the 16 consecutive rows r0..r0+15 (r0 a multiple of 4).
+__device__ __forceinline__ bf16x8_t tr_frag_swz(const unsigned char* tile, int r0, int c0, int lane) {
+    const int j = lane & 15, q = lane >> 4;
+    const int c = c0 + (q & 1) * 16 + 4 * (j & 3);       // first of 4 columns
+    const int r = r0 + (q >> 1) * 8 + (j >> 2);          // r & 3 == (j >> 2) & 3
+    const int pos = (c >> 3) ^ (4 * (r & 3));
+    const unsigned char* p = tile + r * 256 + pos * 16 + (c & 7) * 2;
+    union { struct { s16x4_t lo, hi; } s; bf16x8_t v; } u;
+    u.s.lo = lds_tr16(reinterpret_cast<const uint16_t*>(p));
+    u.s.hi = lds_tr16(reinterpret_cast<const uint16_t*>(p + 4 * 256));   // rows +4: same r & 3
+    return u.v;
+}
+
+// 64 bytes of zeros (never written): the source of direct-to-LDS loads that fall outside a matrix
+static __device__ u32x4_t g_zero_chunk[4];
+
+#define GLB_PTR(p) ((__attribute__((address_space(1))) const void*)(p))
+// s_waitcnt immediate for gfx9: vmcnt in bits [3:0] and [15:14], expcnt [6:4] (no wait), lgkmcnt [11:8] = 0
+constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4); }
+
 // Workgroups go round-robin over the 8 XCDs, each with its own L2: give every
 // XCD one contiguous run of tiles so that neighbouring tiles (which share an
 // operand panel) meet in the same L2.

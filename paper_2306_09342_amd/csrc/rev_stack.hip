@@ -105,9 +105,8 @@ struct Layout {
     int64_t gy1b;          // act-typed copy of gY1 (bf16 mode)
     int64_t dh, dn, dO, dqkv, delta;
     int64_t part_ln, part_col, part_wg;
-    int64_t wT;            // transposed weights (bf16 mode): per block WqkvT | WprojT | W1T | W2T
     int64_t total;
-    int64_t part_wg_elems, wT_block;
+    int64_t part_wg_elems;
 };
 
 static Layout make_layout(const rev_cfg& c) {
@@ -151,8 +150,10 @@ static Layout make_layout(const rev_cfg& c) {
         int64_t e = colsum_partial_elems((int)M, (int)D);
         int64_t e2 = colsum_partial_elems((int)M, (int)Dm);
         int64_t e3 = colsum_partial_elems((int)M, (int)(3 * D));
+        int64_t e4 = (int64_t)gemm_colsum_strips_max((int)M) * Dm;     // fused bias-gradient strips
         if (e2 > e) e = e2;
         if (e3 > e) e = e3;
+        if (e4 > e) e = e4;
         L.part_col = take(e * 4);
     }
     if (c.mode == REV_MODE_BF16) {
@@ -165,8 +166,6 @@ static Layout make_layout(const rev_cfg& c) {
         if (e4 > e) e = e4;
         L.part_wg_elems = e;
         L.part_wg = take(e * 4);
-        L.wT_block = 4 * D * D + 2 * D * Dm;
-        L.wT = take(L.wT_block * c.n_blocks * es);
     }
     L.total = off;
     return L;
@@ -230,16 +229,6 @@ struct Runner {
     template <typename U> U* at(int64_t off) const { return reinterpret_cast<U*>(ws + off); }
     const T* P(int blk, int t) const { return params + (int64_t)blk * block_params(c) + tensor_offset(c, t); }
     float* G(int blk, int t) const { return dparams + (int64_t)blk * block_params(c) + tensor_offset(c, t); }
-    // transposed weight copies (bf16 mode): [in, out] row-major
-    const T* WT(int blk, int which) const {
-        int64_t o = (int64_t)blk * L.wT_block;
-        const int64_t DD = (int64_t)D * D;
-        if (which >= 1) o += 3 * DD;                 // after WqkvT
-        if (which >= 2) o += DD;                     // after WprojT
-        if (which >= 3) o += (int64_t)D * Dm;        // after W1T
-        return at<T>(L.wT) + o;
-    }
-
     struct Slot { T *n2, *h, *a, *n1, *qkv, *o; float *lse, *st1, *st2; };
     Slot slot(int i) const {
         int64_t b = L.slot[i & 1];
@@ -285,22 +274,10 @@ struct Runner {
         return f_post(s, blk, sl, y1, x1, -1.f);
     }
 
-    int transpose_weights(hipStream_t s) {
+    // dA[M,Kin] = dC[M,Nout] * W[Nout,Kin], the weight read as it is stored
+    int dgrad(hipStream_t s, int blk, int wt, const T* dC, int Nout, int Kin, const Epi& e) {
         if constexpr (kBf16) {
-            for (int blk = 0; blk < c.n_blocks; ++blk) {
-                RC(transpose_bf16(s, P(blk, T_WQKV), const_cast<T*>(WT(blk, 0)), 3 * D, D));
-                RC(transpose_bf16(s, P(blk, T_WPROJ), const_cast<T*>(WT(blk, 1)), D, D));
-                RC(transpose_bf16(s, P(blk, T_WFC1), const_cast<T*>(WT(blk, 2)), Dm, D));
-                RC(transpose_bf16(s, P(blk, T_WFC2), const_cast<T*>(WT(blk, 3)), D, Dm));
-            }
-        }
-        return REV_OK;
-    }
-
-    // dA[M,Kin] = dC[M,Nout] * W[Nout,Kin]   (which: index of W's transposed copy)
-    int dgrad(hipStream_t s, int blk, int wt, int which, const T* dC, int Nout, int Kin, const Epi& e) {
-        if constexpr (kBf16) {
-            return gemm_nt_bf16(s, dC, Nout, WT(blk, which), Nout, M, Kin, Nout, e);
+            return gemm_nn_bf16(s, dC, Nout, P(blk, wt), Kin, M, Kin, Nout, e);
         } else {
             return gemm_nn_f32(s, dC, Nout, P(blk, wt), Kin, M, Kin, Nout, e);
         }
@@ -321,31 +298,35 @@ struct Runner {
         float* pwg = kBf16 ? at<float>(L.part_wg) : nullptr;
         T* gy1b = kBf16 ? at<T>(L.gy1b) : reinterpret_cast<T*>(o1);
 
-        // ---- G branch: dh = (dY2 W2) * gelu'(h)
+        // ---- G branch: dh = (dY2 W2) * gelu'(h); the bias gradient of fc1 (column sums of dh) rides
+        // in the epilogue of the matrix-core kernel, otherwise it is a separate pass
         Epi e = {}; e.kind = EPI_GELU_BWD; e.out = dhb; e.aux = sl.h; e.ldo = Dm;
-        RC(dgrad(s, blk, T_WFC2, 3, d2b, D, Dm, e));
+        bool fused_db1 = false;
+        if constexpr (kBf16) fused_db1 = gemm_bf16_fast_path(d2b, D, P(blk, T_WFC2), Dm, Dm, D, e);
+        if (fused_db1) e.colsum = pcol;
+        RC(dgrad(s, blk, T_WFC2, d2b, D, Dm, e));
+        if (fused_db1) RC(reduce_rows(s, pcol, gemm_colsum_strips(M), Dm, Dm, G(blk, T_BFC1)));
+        else RC(colsum<T>(s, dhb, Dm, M, Dm, G(blk, T_BFC1), pcol));
         RC(Ops<T>::wgrad(s, d2b, D, sl.a, Dm, M, D, Dm, G(blk, T_WFC2), pwg, L.part_wg_elems));
-        RC(colsum<float>(s, d2, D, M, D, G(blk, T_BFC2), pcol));
         Epi p = {}; p.kind = EPI_PLAIN; p.out = dn; p.ldo = D;
-        RC(dgrad(s, blk, T_WFC1, 2, dhb, Dm, D, p));
+        RC(dgrad(s, blk, T_WFC1, dhb, Dm, D, p));
         RC(Ops<T>::wgrad(s, dhb, Dm, sl.n2, D, M, Dm, D, G(blk, T_WFC1), pwg, L.part_wg_elems));
-        RC(colsum<T>(s, dhb, Dm, M, Dm, G(blk, T_BFC1), pcol));
-        // gY1 = dY1 + LN2bwd(dn)
+        // gY1 = dY1 + LN2bwd(dn); its column sums are the bias gradient of the projection
         RC((ln_backward<T, T>(s, dn, y1, sl.st2, P(blk, T_LN2G), d1, o1, kBf16 ? gy1b : nullptr,
-                              G(blk, T_LN2G), G(blk, T_LN2B), pln, M, D)));
+                              G(blk, T_LN2G), G(blk, T_BPROJ), pln, M, D)));
         // ---- F branch
         Epi q = {}; q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
-        RC(dgrad(s, blk, T_WPROJ, 1, gy1b, D, D, q));
+        RC(dgrad(s, blk, T_WPROJ, gy1b, D, D, q));
         RC(Ops<T>::wgrad(s, gy1b, D, sl.o, D, M, D, D, G(blk, T_WPROJ), pwg, L.part_wg_elems));
-        RC(colsum<float>(s, o1, D, M, D, G(blk, T_BPROJ), pcol));
         RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh)));
         Epi r = {}; r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
-        RC(dgrad(s, blk, T_WQKV, 0, dqkv, 3 * D, D, r));
+        RC(dgrad(s, blk, T_WQKV, dqkv, 3 * D, D, r));
         RC(Ops<T>::wgrad(s, dqkv, 3 * D, sl.n1, D, M, 3 * D, D, G(blk, T_WQKV), pwg, L.part_wg_elems));
         RC(colsum<T>(s, dqkv, 3 * D, M, 3 * D, G(blk, T_BQKV), pcol));
-        // dX2 = dY2 + LN1bwd(dn)
+        // dX2 = dY2 + LN1bwd(dn); dX2 is the block below's dY2, so its column sums are that block's
+        // fc2 bias gradient
         RC((ln_backward<T, T>(s, dn, x2, sl.st1, P(blk, T_LN1G), d2, o2, kBf16 ? o2b : nullptr,
-                              G(blk, T_LN1G), G(blk, T_LN1B), pln, M, D)));
+                              G(blk, T_LN1G), blk > 0 ? G(blk - 1, T_BFC2) : nullptr, pln, M, D)));
         return REV_OK;
     }
 
@@ -372,7 +353,9 @@ struct Runner {
         }
         const T* top2b = nullptr;
         if (doV) {
-            RC(transpose_weights(sv));
+            // fc2 bias gradient of the top block: column sums of the incoming dY2 (lower blocks get
+            // theirs from the LayerNorm-backward kernel that produces their dY2)
+            RC(colsum<float>(sv, dY2, D, M, D, G(N - 1, T_BFC2), at<float>(L.part_col)));
             if constexpr (kBf16) {
                 T* b = at<T>(L.cot2b[N & 1]);
                 RC(convert_f32_to_bf16(sv, dY2, b, (int64_t)M * D));

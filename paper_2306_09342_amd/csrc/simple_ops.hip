@@ -112,6 +112,10 @@ int gemm_nt_bf16_simple(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
                         int M, int N, int K, const Epi& epi) {
     return launch_simple<bf16, false, true>(s, K_GEMM_NT, A, lda, B, ldb, M, N, K, epi);
 }
+int gemm_nn_bf16_simple(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
+                        int M, int N, int K, const Epi& epi) {
+    return launch_simple<bf16, false, false>(s, K_GEMM_NT, A, lda, B, ldb, M, N, K, epi);
+}
 int gemm_wgrad_f32(hipStream_t s, const float* G, int64_t ldg, const float* A, int64_t lda,
                    int M, int N, int K, float* dW, float*, int64_t) {
     Epi e = {};
