@@ -26,6 +26,11 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 PEAK_FP32_TFLOPS = 157.3      # vector/matrix fp32
 PEAK_HBM_GBS = 8000.0
 
+# Fabric-side bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter
+# reads for a plain 256 MiB device copy), averaged over the launches of the kernel family; measured
+# offline with the commands in profiles/vit_b_backward_reprop_hbm_traffic_pmc.txt.
+MEASURED_TRAFFIC_BYTES = {"vit_b": {"gemm_nt": 2.165e8}}
+
 
 def algorithmic_flops(cfg):
     """Backward-path flops: per block one forward unit of recomputation and two of
@@ -44,6 +49,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vit_b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", choices=["all", "reprop", "pareprop"], default="all",
+                    help="restrict the run to one schedule (for profiler runs); the JSON line then lacks the other")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples the oracle is timed on (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -106,6 +113,26 @@ def main():
         ms = np.array([a.elapsed_time(b) for a, b in per])
         return wall, ms
 
+    def calibration_copy():
+        # one plain device copy of known size (256 MiB read + 256 MiB written): the yardstick the HBM
+        # byte counters of a profiler run are scaled by
+        cal_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+
+    if args.only != "all":
+        fn = reprop if args.only == "reprop" else pareprop
+        wall, ms = timed(fn, args.steps, args.warmup)
+        calibration_copy()
+        print(json.dumps({"metric": f"reversible backward samples/s ({args.only} only), {args.workload}",
+                          "value": Bsz * args.steps / wall, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True,
+                          "scaling": "weak", "vs_baseline": None, "dtype": cfg["mode"], "data": "synthetic",
+                          "config": {"workload": args.workload, "schedule": args.only},
+                          "ms_median": float(np.median(ms))}))
+        return
+
     wall_p, ms_p = timed(pareprop, args.steps, args.warmup)
     wall_r, ms_r = timed(reprop, args.steps, args.warmup)
     _, ms_rc = timed(chain(0), max(3, args.steps // 3), 2)
@@ -117,6 +144,8 @@ def main():
     for _ in range(prof_steps):
         reprop()
     fam = B.rev_profile_end()
+
+    calibration_copy()
 
     flops = algorithmic_flops(cfg)
     ms_step = wall_p / args.steps * 1e3
@@ -144,7 +173,10 @@ def main():
         "frac": achieved / (peak if is_flops_d else PEAK_HBM_GBS),
         "avg_launch_ms": ms_d / n_d,
         "work_per_launch": work_d / n_d,
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dom),
+        "launches_per_step": n_d / prof_steps,
+        "note": "family average over all launches of the dominant kernel family in a Reprop pass, each "
+                "bracketed by HIP events on its own stream",
     }
 
     hidden = (float(np.median(ms_r)) - float(np.median(ms_p))) / float(np.median(ms_rc))

@@ -101,7 +101,7 @@ __device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_
 template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                     const bf16* __restrict__ B, int64_t ldb,
-                                                                    int M, int N, int K, Epi epi) {
+                                                                    int M, int N, int K, Epi epi, int gn) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int ROWB = BK * 2;                         // bytes per tile row
@@ -121,9 +121,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int g = lane >> 5;
-    const int tiles_n = (N + BN - 1) / BN;
+    // Tile order: column groups of `gn` n-tiles, each group walked over all m-tiles, n fastest inside
+    // a group; every XCD gets one contiguous run of that order.  The weight slice of a group
+    // (gn * BN rows of B) then stays in the XCD's L2 while the activation panels stream past it.
+    const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+    const int per_group = gn * tiles_m;
+    const int grp = tile / per_group, in_grp = tile - grp * per_group;
+    const int gw = min(gn, tiles_n - grp * gn);              // width of this (possibly last, narrower) group
+    const int m0 = (in_grp / gw) * BM, n0 = (grp * gn + in_grp % gw) * BN;
 
     // chunk c of row r is kept at position c ^ swz(r): 16 consecutive rows x one chunk -> 16 distinct bank groups
     auto swz = [](int r) { return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
@@ -196,20 +202,28 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
 #if defined(REV_EXP_NOCOMPUTE)
         if (kt >= 0) continue;
 #endif
+        // fragments of step kk+1 are requested before the products of step kk are issued
+        bf16x8_t a[2][TM], b[2][TN];
+        auto load_frags = [&](int kk, int slot) {
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8_t a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * ROWB + koff[kk]);
+            for (int i = 0; i < TM; ++i)
+                a[slot][i] = *reinterpret_cast<const bf16x8_t*>(st + a_row + i * 32 * ROWB + koff[kk]);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                if (BKM) b[j] = tr_frag_swz(st + A_BYTES, kk * 16, wn * TN * 32 + j * 32, lane);
-                else b[j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * ROWB + koff[kk]);
+                if (BKM) b[slot][j] = tr_frag_swz(st + A_BYTES, kk * 16, wn * TN * 32 + j * 32, lane);
+                else b[slot][j] = *reinterpret_cast<const bf16x8_t*>(st + b_row + j * 32 * ROWB + koff[kk]);
             }
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);       // keep the LDS reads ahead of the products that hide them
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int i = 0; i < TM; ++i) acc[j][i] = mfma32(b[j], a[i], acc[j][i]);
+                for (int i = 0; i < TM; ++i) acc[j][i] = mfma32(b[kk & 1][j], a[kk & 1][i], acc[j][i]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -258,6 +272,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     }
 }
 
+int g_nt_group = 0;     // tuning hook: n-tiles per column group (0 = automatic)
+
 template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 static int launch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                       const Epi& epi) {
@@ -271,8 +287,13 @@ static int launch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, 
         REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
         attr_set = true;
     }
-    const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-    hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * 64), shmem, s, A, lda, B, ldb, M, N, K, epi);
+    const int tiles_n = (N + BN - 1) / BN;
+    const int tiles = ((M + BM - 1) / BM) * tiles_n;
+    // group width: keep the group's slice of B (gn * BN * K bf16) near 1.5 MB, well inside a 4 MB L2
+    int gn = g_nt_group > 0 ? g_nt_group : (int)((1536 * 1024) / ((int64_t)BN * K * 2));
+    if (gn < 1) gn = 1;
+    if (gn > tiles_n) gn = tiles_n;
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * 64), shmem, s, A, lda, B, ldb, M, N, K, epi, gn);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
