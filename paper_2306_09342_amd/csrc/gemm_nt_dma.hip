@@ -227,6 +227,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         }
     }
 
+#if defined(REV_EXP_NOEPI)
+    {   // timing experiment: keep the accumulators alive, store (almost) nothing
+        float sacc = 0.f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sacc += acc[j][i][v];
+        if (sacc == 12345.678f && epi.outf) epi.outf[0] = sacc;
+        return;
+    }
+#endif
     // ---- epilogue through LDS, 32 rows at a time: wavefront-private [32][TN*32 + 4] float32 ----
     constexpr int CW = TN * 32, CP = CW + 4;
     constexpr int LPR = CW / 4;                           // lanes per row
@@ -259,8 +272,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         }
     }
     // fused bias gradient: column sums of this wavefront's 64-row strip, lanes folded in a fixed order
-    if (KIND == EPI_GELU_BWD && epi.colsum != nullptr) {
-        static_assert(KIND != EPI_GELU_BWD || TM * 32 == 64, "column-sum strips are 64 rows");
+    if (KIND == EPI_GELU_BWD && TM * 32 == 64 && epi.colsum != nullptr) {   // strips are 64 rows
 #pragma unroll
         for (int off = LPR; off < 64; off <<= 1)
 #pragma unroll
@@ -312,6 +324,12 @@ static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
                         const Epi& epi) {
     switch (g_nt_variant) {
         case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+#ifdef REV_TUNE_VARIANTS
+        case 21: return launch_dma<128, 128, 2, 2, 64, 3, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+        case 22: return launch_dma<128, 128, 2, 2, 64, 4, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+        case 23: return launch_dma<256, 256, 2, 4, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
+        case 24: return launch_dma<256, 256, 2, 4, 32, 4, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
+#endif
         default: return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
     }
 }

@@ -102,8 +102,9 @@ struct Layout {
     int64_t ring[3][2];
     int64_t cot[2][2];     // float32 cotangent levels
     int64_t cot2b[2];      // act-typed copy of the stream-2 cotangent (bf16 mode)
-    int64_t gy1b;          // act-typed copy of gY1 (bf16 mode)
-    int64_t dh, dn, dO, dqkv, delta;
+    int64_t gy1b[2];       // act-typed copy of gY1 (bf16 mode), by block parity
+    int64_t dh[2], dqkv[2]; // by block parity: read by the weight-gradient kernels of the block
+    int64_t dn, dO, delta;
     int64_t part_ln, part_col, part_wg;
     int64_t total;
     int64_t part_wg_elems;
@@ -138,12 +139,15 @@ static Layout make_layout(const rev_cfg& c) {
     if (c.mode == REV_MODE_BF16) {
         L.cot2b[0] = take(M * D * es);
         L.cot2b[1] = take(M * D * es);
-        L.gy1b = take(M * D * es);
+        L.gy1b[0] = take(M * D * es);
+        L.gy1b[1] = take(M * D * es);
     }
-    L.dh = take(M * Dm * es);
+    for (int r = 0; r < 2; ++r) {
+        L.dh[r] = take(M * Dm * es);
+        L.dqkv[r] = take(M * 3 * D * es);
+    }
     L.dn = take(M * D * es);
     L.dO = take(M * D * es);
-    L.dqkv = take(M * 3 * D * es);
     L.delta = take((int64_t)c.batch * c.n_heads * c.seq_len * 4);
     L.part_ln = take(ln_bwd_partial_elems((int)M, (int)D) * 4);
     {
@@ -283,20 +287,27 @@ struct Runner {
         }
     }
 
-    // V_i.  y1: first stream of the block's outputs, x2: second stream of its inputs.
+    // V_i is issued as two kernel sequences.
+    //   grad_d: the input-gradient chain (everything the next block down waits for) plus the cheap
+    //           vector/bias gradients that fall out of its kernels;
+    //   grad_w: the four weight-gradient GEMMs, which only consume what grad_d and R_i produced.
+    // Under PaReprop grad_w rides on the recompute stream, so it overlaps the chain of the same block.
+    // y1: first stream of the block's outputs, x2: second stream of its inputs.
     // d1, d2: incoming cotangents (float32); d2b: act-typed copy of d2.
     // o1, o2: outgoing cotangents; o2b: act-typed copy of o2 (nullable).
-    int grad(hipStream_t s, int blk, const float* y1, const float* x2, const float* d1, const float* d2,
-             const T* d2b, float* o1, float* o2, T* o2b) {
+    // ev (nullable): 3 events recorded on s when dh / gY1 / dqkv are complete.
+    T* gy1_act(int blk, float* o1) const { return kBf16 ? at<T>(L.gy1b[blk & 1]) : reinterpret_cast<T*>(o1); }
+
+    int grad_d(hipStream_t s, int blk, const float* y1, const float* x2, const float* d1, const float* d2,
+               const T* d2b, float* o1, float* o2, T* o2b, const hipEvent_t* ev) {
         Slot sl = slot(blk);
-        T* dhb = at<T>(L.dh);
+        T* dhb = at<T>(L.dh[blk & 1]);
+        T* dqkv = at<T>(L.dqkv[blk & 1]);
         T* dn = at<T>(L.dn);
         T* dO = at<T>(L.dO);
-        T* dqkv = at<T>(L.dqkv);
         float* pcol = at<float>(L.part_col);
         float* pln = at<float>(L.part_ln);
-        float* pwg = kBf16 ? at<float>(L.part_wg) : nullptr;
-        T* gy1b = kBf16 ? at<T>(L.gy1b) : reinterpret_cast<T*>(o1);
+        T* gy1b = gy1_act(blk, o1);
 
         // ---- G branch: dh = (dY2 W2) * gelu'(h); the bias gradient of fc1 (column sums of dh) rides
         // in the epilogue of the matrix-core kernel, otherwise it is a separate pass
@@ -305,28 +316,47 @@ struct Runner {
         if constexpr (kBf16) fused_db1 = gemm_bf16_fast_path(d2b, D, P(blk, T_WFC2), Dm, Dm, D, e);
         if (fused_db1) e.colsum = pcol;
         RC(dgrad(s, blk, T_WFC2, d2b, D, Dm, e));
+        if (ev) REV_HIP(hipEventRecord(ev[0], s));
         if (fused_db1) RC(reduce_rows(s, pcol, gemm_colsum_strips(M), Dm, Dm, G(blk, T_BFC1)));
         else RC(colsum<T>(s, dhb, Dm, M, Dm, G(blk, T_BFC1), pcol));
-        RC(Ops<T>::wgrad(s, d2b, D, sl.a, Dm, M, D, Dm, G(blk, T_WFC2), pwg, L.part_wg_elems));
         Epi p = {}; p.kind = EPI_PLAIN; p.out = dn; p.ldo = D;
         RC(dgrad(s, blk, T_WFC1, dhb, Dm, D, p));
-        RC(Ops<T>::wgrad(s, dhb, Dm, sl.n2, D, M, Dm, D, G(blk, T_WFC1), pwg, L.part_wg_elems));
         // gY1 = dY1 + LN2bwd(dn); its column sums are the bias gradient of the projection
         RC((ln_backward<T, T>(s, dn, y1, sl.st2, P(blk, T_LN2G), d1, o1, kBf16 ? gy1b : nullptr,
                               G(blk, T_LN2G), G(blk, T_BPROJ), pln, M, D)));
+        if (ev) REV_HIP(hipEventRecord(ev[1], s));
         // ---- F branch
         Epi q = {}; q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
         RC(dgrad(s, blk, T_WPROJ, gy1b, D, D, q));
-        RC(Ops<T>::wgrad(s, gy1b, D, sl.o, D, M, D, D, G(blk, T_WPROJ), pwg, L.part_wg_elems));
         RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh)));
+        if (ev) REV_HIP(hipEventRecord(ev[2], s));
         Epi r = {}; r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
         RC(dgrad(s, blk, T_WQKV, dqkv, 3 * D, D, r));
-        RC(Ops<T>::wgrad(s, dqkv, 3 * D, sl.n1, D, M, 3 * D, D, G(blk, T_WQKV), pwg, L.part_wg_elems));
         RC(colsum<T>(s, dqkv, 3 * D, M, 3 * D, G(blk, T_BQKV), pcol));
         // dX2 = dY2 + LN1bwd(dn); dX2 is the block below's dY2, so its column sums are that block's
         // fc2 bias gradient
         RC((ln_backward<T, T>(s, dn, x2, sl.st1, P(blk, T_LN1G), d2, o2, kBf16 ? o2b : nullptr,
                               G(blk, T_LN1G), blk > 0 ? G(blk - 1, T_BFC2) : nullptr, pln, M, D)));
+        return REV_OK;
+    }
+
+    // ev (nullable): events to wait for on s before the kernels that read dY2 copy / dh / gY1 / dqkv
+    // (4 events); done_w2 (nullable) is recorded after the fc2 weight gradient.
+    int grad_w(hipStream_t s, int blk, const T* d2b, float* o1, const hipEvent_t* ev, hipEvent_t done_w2) {
+        Slot sl = slot(blk);
+        T* dhb = at<T>(L.dh[blk & 1]);
+        T* dqkv = at<T>(L.dqkv[blk & 1]);
+        float* pwg = kBf16 ? at<float>(L.part_wg) : nullptr;
+        T* gy1b = gy1_act(blk, o1);
+        if (ev) REV_HIP(hipStreamWaitEvent(s, ev[0], 0));
+        RC(Ops<T>::wgrad(s, d2b, D, sl.a, Dm, M, D, Dm, G(blk, T_WFC2), pwg, L.part_wg_elems));
+        if (done_w2) REV_HIP(hipEventRecord(done_w2, s));
+        if (ev) REV_HIP(hipStreamWaitEvent(s, ev[1], 0));
+        RC(Ops<T>::wgrad(s, dhb, Dm, sl.n2, D, M, Dm, D, G(blk, T_WFC1), pwg, L.part_wg_elems));
+        if (ev) REV_HIP(hipStreamWaitEvent(s, ev[2], 0));
+        RC(Ops<T>::wgrad(s, gy1b, D, sl.o, D, M, D, D, G(blk, T_WPROJ), pwg, L.part_wg_elems));
+        if (ev) REV_HIP(hipStreamWaitEvent(s, ev[3], 0));
+        RC(Ops<T>::wgrad(s, dqkv, 3 * D, sl.n1, D, M, 3 * D, D, G(blk, T_WQKV), pwg, L.part_wg_elems));
         return REV_OK;
     }
 
@@ -339,15 +369,29 @@ struct Runner {
     }
 
     // schedule: 0 = Reprop, 1 = PaReprop, 2 = R chain only, 3 = V chain only
+    //
+    // PaReprop, stream by stream (block indices 1-based, N at the top):
+    //   sr:  R_N | R_{N-1}  W_N | R_{N-2}  W_{N-1} | ...      (W_i = grad_w of block i)
+    //   sv:  D_N | D_{N-1}      | D_{N-2}          | ...      (D_i = grad_d of block i)
+    // Orderings across the streams (events):
+    //   D_i  after R_i                      (activations of block i exist)
+    //   D_i  after W_{i+2}                  (dh/dqkv/gY1 buffers of the same parity are free again)
+    //   D_i  after the fc2 weight gradient of W_{i+1}   (it reads the dY2 copy that D_i's last kernel rewrites)
+    //   R_i  after D_{i+2}                  (slot i mod 2 and ring level i+2 are free; W_{i+2} precedes R_i on sr)
+    //   each GEMM of W_i after the kernel of D_i that produces its cotangent operand
+    // and sv finally waits for W_1, so everything is ordered before later work on sv.
     int backward(int schedule, const float* Y1, const float* Y2, const float* dY1, const float* dY2,
                  float* dX1, float* dX2, float* X1o, float* X2o, hipStream_t sv, hipStream_t sr) {
         const int N = c.n_blocks;
         const bool doR = schedule != 3, doV = schedule != 2;
+        // per block: 0 R done, 1 D done, 2 W done, 3 dY2 copy ready (= D start), 4 dh, 5 gY1, 6 dqkv, 7 fc2 wgrad done
+        constexpr int EPB = 8;
         std::vector<hipEvent_t> ev;
+        auto E = [&](int i, int k) { return ev[(i - 1) * EPB + k]; };
         if (schedule == 1) {
-            RC(get_events(2 * N + 2, ev));
-            REV_HIP(hipEventRecord(ev[2 * N], sv));            // fork
-            REV_HIP(hipStreamWaitEvent(sr, ev[2 * N], 0));
+            RC(get_events(EPB * N + 1, ev));
+            REV_HIP(hipEventRecord(ev[EPB * N], sv));            // fork
+            REV_HIP(hipStreamWaitEvent(sr, ev[EPB * N], 0));
         } else {
             sr = sv;
         }
@@ -369,40 +413,51 @@ struct Runner {
             const float* y2 = (i == N) ? Y2 : res(i, 1, X1o, X2o);
             return recompute(sr, i - 1, y1, y2, res(i - 1, 0, X1o, X2o), res(i - 1, 1, X1o, X2o));
         };
-        auto run_V = [&](int i) -> int {
+        auto d2b_of = [&](int i) -> const T* {
+            if constexpr (kBf16) return (i == N) ? top2b : at<T>(L.cot2b[i & 1]);
+            else return reinterpret_cast<const T*>((i == N) ? dY2 : at<float>(L.cot[i & 1][1]));
+        };
+        auto o1_of = [&](int i) -> float* { return (i == 1) ? dX1 : at<float>(L.cot[(i - 1) & 1][0]); };
+        auto run_D = [&](int i, const hipEvent_t* evs) -> int {
             const float* y1 = (i == N) ? Y1 : res(i, 0, X1o, X2o);
             const float* x2 = res(i - 1, 1, X1o, X2o);
             const float* d1 = (i == N) ? dY1 : at<float>(L.cot[i & 1][0]);
             const float* d2 = (i == N) ? dY2 : at<float>(L.cot[i & 1][1]);
-            const T* d2b;
-            if constexpr (kBf16) d2b = (i == N) ? top2b : at<T>(L.cot2b[i & 1]);
-            else d2b = reinterpret_cast<const T*>(d2);
-            float* o1 = (i == 1) ? dX1 : at<float>(L.cot[(i - 1) & 1][0]);
             float* o2 = (i == 1) ? dX2 : at<float>(L.cot[(i - 1) & 1][1]);
             T* o2b = nullptr;
             if constexpr (kBf16) o2b = (i == 1) ? nullptr : at<T>(L.cot2b[(i - 1) & 1]);
-            return grad(sv, i - 1, y1, x2, d1, d2, d2b, o1, o2, o2b);
+            return grad_d(sv, i - 1, y1, x2, d1, d2, d2b_of(i), o1_of(i), o2, o2b, evs);
         };
         if (schedule == 1) {
-            // R chain on sr, V chain on sv.  ev[i-1]: R_i done; ev[N+i-1]: V_i done.
+            RC(run_R(N));
+            REV_HIP(hipEventRecord(E(N, 0), sr));
             for (int i = N; i >= 1; --i) {
-                if (i + 2 <= N) REV_HIP(hipStreamWaitEvent(sr, ev[N + (i + 2) - 1], 0));   // slot (and ring level) free
-                RC(run_R(i));
-                REV_HIP(hipEventRecord(ev[i - 1], sr));
-                // enqueue V_{i+1} after R_i so the host feeds both streams in step
-                if (i + 1 <= N) {
-                    REV_HIP(hipStreamWaitEvent(sv, ev[(i + 1) - 1], 0));
-                    RC(run_V(i + 1));
-                    REV_HIP(hipEventRecord(ev[N + (i + 1) - 1], sv));
+                // ---- D_i on the gradient stream
+                REV_HIP(hipStreamWaitEvent(sv, E(i, 0), 0));
+                if (i + 2 <= N) REV_HIP(hipStreamWaitEvent(sv, E(i + 2, 2), 0));
+                if (i + 1 <= N) REV_HIP(hipStreamWaitEvent(sv, E(i + 1, 7), 0));
+                REV_HIP(hipEventRecord(E(i, 3), sv));
+                const hipEvent_t dev[3] = {E(i, 4), E(i, 5), E(i, 6)};
+                RC(run_D(i, dev));
+                REV_HIP(hipEventRecord(E(i, 1), sv));
+                // ---- R_{i-1}, then W_i, on the recompute stream
+                if (i - 1 >= 1) {
+                    if (i + 1 <= N) REV_HIP(hipStreamWaitEvent(sr, E(i + 1, 1), 0));
+                    RC(run_R(i - 1));
+                    REV_HIP(hipEventRecord(E(i - 1, 0), sr));
                 }
+                const hipEvent_t wev[4] = {E(i, 3), E(i, 4), E(i, 5), E(i, 6)};
+                RC(grad_w(sr, i - 1, d2b_of(i), o1_of(i), wev, E(i, 7)));
+                REV_HIP(hipEventRecord(E(i, 2), sr));
             }
-            REV_HIP(hipStreamWaitEvent(sv, ev[0], 0));
-            RC(run_V(1));
-            // join: sr's last work (R_1) is already ordered before V_1 on sv
+            REV_HIP(hipStreamWaitEvent(sv, E(1, 2), 0));          // join (W_2 precedes W_1 on sr)
         } else {
             for (int i = N; i >= 1; --i) {
                 if (doR) RC(run_R(i));
-                if (doV) RC(run_V(i));
+                if (doV) {
+                    RC(run_D(i, nullptr));
+                    RC(grad_w(sv, i - 1, d2b_of(i), o1_of(i), nullptr, nullptr));
+                }
             }
         }
         return REV_OK;
