@@ -22,24 +22,22 @@
 
 namespace rev {
 
-// erf by the five-term rational-exponential formula (Abramowitz & Stegun 7.1.26,
-// |error| < 1.5e-7), sharing exp(-x^2/2) between GELU and its derivative.
-struct GeluParts { float cdf, pdf; };
-__device__ __forceinline__ GeluParts gelu_parts(float x) {
-    const float ax = fabsf(x);
-    const float e = __expf(-0.5f * x * x);                       // exp(-z^2), z = |x| / sqrt(2)
-    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * 0.70710678118654752f * ax);
-    float poly = 1.061405429f;
-    poly = poly * t - 1.453152027f;
-    poly = poly * t + 1.421413741f;
-    poly = poly * t - 0.284496736f;
-    poly = poly * t + 0.254829592f;
-    const float erfa = 1.0f - poly * t * e;                       // erf(z) for z >= 0
-    GeluParts r;
-    r.cdf = 0.5f * (1.0f + copysignf(erfa, x));
-    r.pdf = 0.39894228040143268f * e;
-    return r;
+// Normal CDF for the bf16 GELU epilogues: Phi(x) = 1/2 + x * P(x^2) on |x| <= 3.8, clamped outside, with a
+// degree-6 minimax-fitted P (|error| < 6.5e-5, below half a bf16 ulp of the value the epilogue
+// stores); plain FMAs, no transcendental.  The density, needed by the derivative only, is one exp.
+__device__ __forceinline__ float gelu_cdf(float x) {
+    const float xc = fminf(fmaxf(x, -3.8f), 3.8f);
+    const float u = xc * xc;
+    float p = 3.665773107e-08f;
+    p = p * u - 2.272460051e-06f;
+    p = p * u + 6.068476796e-05f;
+    p = p * u - 9.315473144e-04f;
+    p = p * u + 9.316634387e-03f;
+    p = p * u - 6.571978331e-02f;
+    p = p * u + 3.986767530e-01f;
+    return 0.5f + xc * p;
 }
+__device__ __forceinline__ float gelu_pdf(float x) { return 0.39894228040143268f * __expf(-0.5f * x * x); }
 
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -63,19 +61,16 @@ __device__ __forceinline__ void st_bf16x4(void* p, f32x4_t v) {
 // 4 consecutive output columns n..n+3 of row m
 // (returns the float32 values behind the stored output, for the fused column sums)
 template <int KIND>
-__device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_t acc) {
+__device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_t acc, f32x4_t bv) {
     const int64_t idx = (int64_t)m * e.ldo + n;
-    if (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) {
-        const f32x4_t bv = ld_bf16x4(reinterpret_cast<const bf16*>(e.bias) + n);
-        acc += bv;
-    }
+    if (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) acc += bv;
     if (KIND == EPI_BIAS) {
         st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
     } else if (KIND == EPI_BIAS_GELU) {
         st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
         f32x4_t a;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) a[k] = acc[k] * gelu_parts(acc[k]).cdf;
+        for (int k = 0; k < 4; ++k) a[k] = acc[k] * gelu_cdf(acc[k]);
         st_bf16x4(reinterpret_cast<bf16*>(e.out2) + idx, a);
     } else if (KIND == EPI_RESIDUAL) {
         const f32x4_t r = *reinterpret_cast<const f32x4_t*>(e.res + idx);
@@ -85,8 +80,7 @@ __device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_
         f32x4_t o;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const GeluParts g = gelu_parts(h[k]);
-            o[k] = acc[k] * (g.cdf + h[k] * g.pdf);
+            o[k] = acc[k] * (gelu_cdf(h[k]) + h[k] * gelu_pdf(h[k]));
         }
         st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, o);
         return o;
@@ -115,7 +109,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     constexpr int LPW = (IA + IB) / NW;                  // ... per wavefront
     static_assert(BK == 64 || BK == 32, "BK");
     static_assert(IA % NW == 0 && IB % NW == 0, "loads must split evenly over the wavefronts");
-    static_assert((NS - 2) * LPW < 64, "vmcnt range");
+    static_assert(NS == 1 || (NS - 2) * LPW < 64, "vmcnt range");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -191,13 +185,24 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int b_row = A_BYTES + (wn * TN * 32 + fr) * ROWB;
 
     for (int kt = 0; kt < nk; ++kt) {
-        // loads of stage kt are older than the (NS-2) stages issued after them
-        if (kt + NS - 2 < nk) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * LPW));
-        else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
-        __builtin_amdgcn_s_barrier();
+        if (NS == 1) {
+            // single buffer: latency is hidden by the other workgroups resident on the CU
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+            __builtin_amdgcn_s_barrier();                 // everybody is done reading the buffer
 #if !defined(REV_EXP_NOLOAD)
-        if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
+            issue(kt, 0);
 #endif
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+            __builtin_amdgcn_s_barrier();
+        } else {
+            // loads of stage kt are older than the (NS-2) stages issued after them
+            if (kt + NS - 2 < nk) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NS > 1 ? (NS - 2) * LPW : 0));
+            else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+            __builtin_amdgcn_s_barrier();
+#if !defined(REV_EXP_NOLOAD)
+            if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
+#endif
+        }
         const unsigned char* st = smem + (kt % NS) * STAGE;
 #if defined(REV_EXP_NOCOMPUTE)
         if (kt >= 0) continue;
@@ -250,6 +255,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int c4 = lane % LPR, rr = lane / LPR;
     const int n = n0 + wn * CW + 4 * c4;
     f32x4_t csum = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t bv = {0.f, 0.f, 0.f, 0.f};                    // this lane's 4 columns never change: one bias load
+    if ((KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) && n < N)
+        bv = ld_bf16x4(reinterpret_cast<const bf16*>(epi.bias) + n);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -266,7 +274,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             const int m = m0 + wm * TM * 32 + i * 32 + row;
             const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ct + row * CP + 4 * c4);
             if (m < M && n < N) {
-                const f32x4_t o = epi_store4<KIND>(epi, m, n, v);
+                const f32x4_t o = epi_store4<KIND>(epi, m, n, v, bv);
                 if (KIND == EPI_GELU_BWD) csum += o;
             }
         }
@@ -325,6 +333,9 @@ static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
     switch (g_nt_variant) {
         case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
 #ifdef REV_TUNE_VARIANTS
+        case 20: return launch_dma<128, 128, 2, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+        case 25: return launch_dma<256, 128, 4, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+        case 26: return launch_dma<256, 128, 2, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
         case 21: return launch_dma<128, 128, 2, 2, 64, 3, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
         case 22: return launch_dma<128, 128, 2, 2, 64, 4, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
         case 23: return launch_dma<256, 256, 2, 4, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
