@@ -42,13 +42,13 @@ __device__ __forceinline__ void load_owned(const bf16* __restrict__ base, int64_
     }
 }
 
-// Cooperative load of AT_ROWS rows [row0, row0+64) of a [nrows, ld] matrix into an LDS tile;
+// Cooperative load of `trows` rows [row0, row0+trows) of a [nrows, ld] matrix into an LDS tile;
 // rows >= nrows and columns >= dh are zero-filled.
 template <int DHP>
 __device__ __forceinline__ void load_tile(uint16_t* tile, const bf16* __restrict__ base, int64_t ld, int row0,
-                                          int nrows, int dh) {
+                                          int nrows, int dh, int trows) {
     constexpr int CH = AtCfg<DHP>::CH, PITCH = AtCfg<DHP>::PITCH;
-    for (int idx = threadIdx.x; idx < AT_ROWS * CH; idx += blockDim.x) {
+    for (int idx = threadIdx.x; idx < trows * CH; idx += blockDim.x) {
         const int row = idx / CH, ch = idx % CH;
         const int gr = row0 + row;
         u32x4_t v = {0u, 0u, 0u, 0u};
@@ -76,11 +76,13 @@ __device__ __forceinline__ void store4_bf16(bf16* p, float a, float b, float c, 
 // ----------------------------------------------------------------------------------------
 template <int DHP>
 __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
-                                                     float* __restrict__ lse, int T, int H, int dh) {
+                                                     float* __restrict__ lse, int T, int H, int dh, int trows) {
+    // trows: streamed rows held in LDS at a time -- 64, or all ceil32(T) rows when they fit (one load, no
+    // further barriers)
     using C = AtCfg<DHP>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* Vs = Ks + AT_ROWS * C::PITCH;
+    uint16_t* Ks0 = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Vs0 = Ks0 + trows * C::PITCH;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int g = lane >> 5;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -100,11 +102,14 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
         for (int v = 0; v < 16; ++v) accO[dt][v] = 0.f;
     float m = -INFINITY, l = 0.f;
 
-    for (int k0 = 0; k0 < T; k0 += AT_ROWS) {
-        __syncthreads();
-        load_tile<DHP>(Ks, base + D, ld, k0, T, dh);
-        load_tile<DHP>(Vs, base + 2 * D, ld, k0, T, dh);
-        __syncthreads();
+    for (int t0 = 0; t0 < T; t0 += trows) {
+      __syncthreads();
+      load_tile<DHP>(Ks0, base + D, ld, t0, T, dh, trows);
+      load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
+      __syncthreads();
+      for (int k0 = t0; k0 < min(T, t0 + trows); k0 += AT_ROWS) {
+        const uint16_t* Ks = Ks0 + (k0 - t0) * C::PITCH;
+        const uint16_t* Vs = Vs0 + (k0 - t0) * C::PITCH;
         const int nt = (T - k0 > 32) ? 2 : 1;
         float s[2][16];
         float mloc = -INFINITY;
@@ -159,6 +164,7 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
                     }
                 }
             }
+      }
     }
     // O^T tile: lane holds query q0 + l%32, features dt*32 + 8*(v/4) + 4g + v%4
     const int q = q0 + (lane & 31);
@@ -185,11 +191,11 @@ template <int DHP>
 __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                         const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                         bf16* __restrict__ dqkv, float* __restrict__ delta,
-                                                        int T, int H, int dh) {
+                                                        int T, int H, int dh, int trows) {
     using C = AtCfg<DHP>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* Vs = Ks + AT_ROWS * C::PITCH;
+    uint16_t* Ks0 = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Vs0 = Ks0 + trows * C::PITCH;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int g = lane >> 5;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -225,11 +231,14 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
 #pragma unroll
         for (int v = 0; v < 16; ++v) accQ[dt][v] = 0.f;
 
-    for (int k0 = 0; k0 < T; k0 += AT_ROWS) {
-        __syncthreads();
-        load_tile<DHP>(Ks, base + D, ld, k0, T, dh);
-        load_tile<DHP>(Vs, base + 2 * D, ld, k0, T, dh);
-        __syncthreads();
+    for (int t0 = 0; t0 < T; t0 += trows) {
+      __syncthreads();
+      load_tile<DHP>(Ks0, base + D, ld, t0, T, dh, trows);
+      load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
+      __syncthreads();
+      for (int k0 = t0; k0 < min(T, t0 + trows); k0 += AT_ROWS) {
+        const uint16_t* Ks = Ks0 + (k0 - t0) * C::PITCH;
+        const uint16_t* Vs = Vs0 + (k0 - t0) * C::PITCH;
         const int nt = (T - k0 > 32) ? 2 : 1;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -262,6 +271,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
                 }
             }
         }
+      }
     }
     if (q < T) {
         bf16* dq = dqkv + ((int64_t)b * T + q) * ld + h * dh;
@@ -282,13 +292,13 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
 template <int DHP>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16* __restrict__ dqkv, int T, int H, int dh) {
+                                                         bf16* __restrict__ dqkv, int T, int H, int dh, int trows) {
     using C = AtCfg<DHP>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* Qs = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* Os = Qs + AT_ROWS * C::PITCH;                       // dO tile
-    float* lse_s = reinterpret_cast<float*>(Os + AT_ROWS * C::PITCH);
-    float* del_s = lse_s + AT_ROWS;
+    uint16_t* Qs0 = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* Os0 = Qs0 + trows * C::PITCH;                       // dO tile
+    float* lse_s0 = reinterpret_cast<float*>(Os0 + trows * C::PITCH);
+    float* del_s0 = lse_s0 + trows;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int g = lane >> 5;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -309,16 +319,21 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
 #pragma unroll
         for (int v = 0; v < 16; ++v) { accK[dt][v] = 0.f; accV[dt][v] = 0.f; }
 
-    for (int i0 = 0; i0 < T; i0 += AT_ROWS) {
-        __syncthreads();
-        load_tile<DHP>(Qs, base, ld, i0, T, dh);
-        load_tile<DHP>(Os, dob, D, i0, T, dh);
-        for (int r = threadIdx.x; r < AT_ROWS; r += blockDim.x) {
-            const int i = i0 + r;
-            lse_s[r] = (i < T) ? lse[(int64_t)bh * T + i] : INFINITY;     // exp(. - inf) = 0 masks the row
-            del_s[r] = (i < T) ? delta[(int64_t)bh * T + i] : 0.f;
-        }
-        __syncthreads();
+    for (int t0 = 0; t0 < T; t0 += trows) {
+      __syncthreads();
+      load_tile<DHP>(Qs0, base, ld, t0, T, dh, trows);
+      load_tile<DHP>(Os0, dob, D, t0, T, dh, trows);
+      for (int r = threadIdx.x; r < trows; r += blockDim.x) {
+          const int i = t0 + r;
+          lse_s0[r] = (i < T) ? lse[(int64_t)bh * T + i] : INFINITY;     // exp(. - inf) = 0 masks the row
+          del_s0[r] = (i < T) ? delta[(int64_t)bh * T + i] : 0.f;
+      }
+      __syncthreads();
+      for (int i0 = t0; i0 < min(T, t0 + trows); i0 += AT_ROWS) {
+        const uint16_t* Qs = Qs0 + (i0 - t0) * C::PITCH;
+        const uint16_t* Os = Os0 + (i0 - t0) * C::PITCH;
+        const float* lse_s = lse_s0 + (i0 - t0);
+        const float* del_s = del_s0 + (i0 - t0);
         const int nt = (T - i0 > 32) ? 2 : 1;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -363,6 +378,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
                 }
             }
         }
+      }
     }
     const int j = j0 + (lane & 31);
     if (j < T) {
@@ -386,18 +402,39 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
 // ----------------------------------------------------------------------------------------
 // Wavefronts per workgroup: split the ceil(T/32) row tiles evenly over as few workgroups as
 // 8 wavefronts each allow (T=197: 1 x 7, T=257: 2 x 5, T=512: 2 x 8).
+#define RC_LDS(expr) do { int _rc = (expr); if (_rc != REV_OK) return _rc; } while (0)
+
 static void row_split(int T, int* nblk, int* nw) {
     const int tiles = (T + 31) / 32;
     *nblk = (tiles + 7) / 8;
     *nw = (tiles + *nblk - 1) / *nblk;
 }
 
+// Rows of the streamed operands kept in LDS at a time: every (32-padded) row of the head when two such
+// tiles plus the row statistics fit in 80 KB -- then a workgroup loads once and never synchronises
+// again -- otherwise 64-row tiles.
+template <int DHP>
+static int tile_rows(int T) {
+    const int all = (T + 31) / 32 * 32;
+    const size_t bytes = (size_t)2 * all * AtCfg<DHP>::PITCH * sizeof(uint16_t) + 2 * all * sizeof(float);
+    return bytes <= 80 * 1024 ? all : AT_ROWS;
+}
+
+template <typename K>
+static int raise_lds(K kern, size_t shmem) {
+    if (shmem > 64 * 1024)
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));
+    return REV_OK;
+}
+
 template <int DHP>
 static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B, int T, int H, int dh) {
     int nblk, nw;
     row_split(T, &nblk, &nw);
-    const size_t shmem = (size_t)2 * AT_ROWS * AtCfg<DHP>::PITCH * sizeof(uint16_t);
-    hipLaunchKernelGGL((attn_fwd_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, lse, T, H, dh);
+    const int trows = tile_rows<DHP>(T);
+    const size_t shmem = (size_t)2 * trows * AtCfg<DHP>::PITCH * sizeof(uint16_t);
+    RC_LDS(raise_lds(attn_fwd_mfma<DHP>, shmem));
+    hipLaunchKernelGGL((attn_fwd_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, lse, T, H, dh, trows);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
@@ -407,11 +444,15 @@ static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16*
                       float* delta, int B, int T, int H, int dh) {
     int nblk, nw;
     row_split(T, &nblk, &nw);
-    const size_t shmem = (size_t)2 * AT_ROWS * AtCfg<DHP>::PITCH * sizeof(uint16_t);
+    const int trows = tile_rows<DHP>(T);
+    const size_t shmem = (size_t)2 * trows * AtCfg<DHP>::PITCH * sizeof(uint16_t);
+    const size_t shmem2 = shmem + 2 * trows * sizeof(float);
+    RC_LDS(raise_lds(attn_bwd_dq_mfma<DHP>, shmem));
+    RC_LDS(raise_lds(attn_bwd_dkv_mfma<DHP>, shmem2));
     hipLaunchKernelGGL((attn_bwd_dq_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, dout, lse, dqkv,
-                       delta, T, H, dh);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem + 2 * AT_ROWS * sizeof(float),
-                       s, qkv, dout, lse, delta, dqkv, T, H, dh);
+                       delta, T, H, dh, trows);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem2, s, qkv, dout, lse, delta,
+                       dqkv, T, H, dh, trows);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
