@@ -90,7 +90,8 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
     const int64_t ld = 3 * (int64_t)D;
     const bf16* base = qkv + (int64_t)b * T * ld + h * dh;
     const int q0 = (blockIdx.x * nw + wave) * 32;
-    const float scale = rsqrtf((float)dh);
+    // scores are kept in the base-2 domain (scale * log2 e folded into one multiply, exp2 is one instruction)
+    const float c2 = rsqrtf((float)dh) * 1.4426950408889634f;
 
     bf16x8_t bq[C::KS];
     load_owned<DHP>(base, ld, q0, T, dh, lane, bq);
@@ -123,24 +124,32 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
 #pragma unroll
                 for (int ks = 0; ks < C::KS; ++ks)
                     acc = mfma32(*reinterpret_cast<const bf16x8_t*>(kp + 16 * ks), bq[ks], acc);
+                if (k0 + t * 32 + 32 <= T) {               // whole tile inside the sequence: no masking
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    s[t][v] = (key < T) ? acc[v] * scale : -INFINITY;
-                    mloc = fmaxf(mloc, s[t][v]);
+                    for (int v = 0; v < 16; ++v) {
+                        s[t][v] = acc[v] * c2;
+                        mloc = fmaxf(mloc, s[t][v]);
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                        s[t][v] = (key < T) ? acc[v] * c2 : -INFINITY;
+                        mloc = fmaxf(mloc, s[t][v]);
+                    }
                 }
             }
         }
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
         const float mn = fmaxf(m, mloc);
-        const float corr = __expf(m - mn);
+        const float corr = __builtin_amdgcn_exp2f(m - mn);
         float lsum = 0.f;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
             if (t < nt) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    s[t][v] = __expf(s[t][v] - mn);
+                    s[t][v] = __builtin_amdgcn_exp2f(s[t][v] - mn);
                     lsum += s[t][v];
                 }
             }
@@ -180,7 +189,7 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
                     store4_bf16(orow + d, accO[dt][4 * v4] * inv, accO[dt][4 * v4 + 1] * inv,
                                 accO[dt][4 * v4 + 2] * inv, accO[dt][4 * v4 + 3] * inv);
             }
-        if (g == 0) lse[(int64_t)bh * T + q] = m + __logf(l);
+        if (g == 0) lse[(int64_t)bh * T + q] = (m + __log2f(l)) * 0.6931471805599453f;   // back to natural log
     }
 }
 
@@ -207,6 +216,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
     const int q0 = (blockIdx.x * nw + wave) * 32;
     const int q = q0 + (lane & 31), qc = min(q, T - 1);
     const float scale = rsqrtf((float)dh);
+    const float c2 = scale * 1.4426950408889634f;
 
     bf16x8_t bq[C::KS], bdo[C::KS];
     load_owned<DHP>(base, ld, q0, T, dh, lane, bq);
@@ -222,7 +232,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
             for (int e = 0; e < 8; ++e) dl += (float)bdo[ks][e] * (float)bo[ks][e];
         dl += __shfl_xor(dl, 32, 64);
     }
-    const float L = lse[(int64_t)bh * T + qc];
+    const float L2 = lse[(int64_t)bh * T + qc] * 1.4426950408889634f;
     if (q < T && g == 0) delta[(int64_t)bh * T + q] = dl;
 
     f32x16_t accQ[C::DT];
@@ -253,12 +263,18 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
                     aS = mfma32(*reinterpret_cast<const bf16x8_t*>(kp + 16 * ks), bq[ks], aS);
                     aP = mfma32(*reinterpret_cast<const bf16x8_t*>(vp + 16 * ks), bdo[ks], aP);
                 }
+                // dS without its 1/sqrt(head_dim): that factor is applied once to the finished dQ
                 float ds[16];
+                if (k0 + t * 32 + 32 <= T) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    const float p = (key < T) ? __expf(aS[v] * scale - L) : 0.f;
-                    ds[v] = p * (aP[v] - dl) * scale;
+                    for (int v = 0; v < 16; ++v)
+                        ds[v] = __builtin_amdgcn_exp2f(aS[v] * c2 - L2) * (aP[v] - dl);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                        ds[v] = (key < T) ? __builtin_amdgcn_exp2f(aS[v] * c2 - L2) * (aP[v] - dl) : 0.f;
+                    }
                 }
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
@@ -281,7 +297,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
             for (int v4 = 0; v4 < 4; ++v4) {
                 const int d = dt * 32 + 8 * v4 + 4 * g;
                 if (d < dh)
-                    store4_bf16(dq + d, accQ[dt][4 * v4], accQ[dt][4 * v4 + 1], accQ[dt][4 * v4 + 2], accQ[dt][4 * v4 + 3]);
+                    store4_bf16(dq + d, accQ[dt][4 * v4] * scale, accQ[dt][4 * v4 + 1] * scale,
+                                accQ[dt][4 * v4 + 2] * scale, accQ[dt][4 * v4 + 3] * scale);
             }
     }
 }
@@ -308,6 +325,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
     const bf16* dob = dout + (int64_t)b * T * D + h * dh;
     const int j0 = (blockIdx.x * nw + wave) * 32;
     const float scale = rsqrtf((float)dh);
+    const float c2 = scale * 1.4426950408889634f;
 
     bf16x8_t bk[C::KS], bv[C::KS];
     load_owned<DHP>(base + D, ld, j0, T, dh, lane, bk);
@@ -325,7 +343,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
       load_tile<DHP>(Os0, dob, D, t0, T, dh, trows);
       for (int r = threadIdx.x; r < trows; r += blockDim.x) {
           const int i = t0 + r;
-          lse_s0[r] = (i < T) ? lse[(int64_t)bh * T + i] : INFINITY;     // exp(. - inf) = 0 masks the row
+          // log-sum-exp in the base-2 domain; +inf masks rows beyond the sequence (exp2(. - inf) = 0)
+          lse_s0[r] = (i < T) ? lse[(int64_t)bh * T + i] * 1.4426950408889634f : INFINITY;
           del_s0[r] = (i < T) ? delta[(int64_t)bh * T + i] : 0.f;
       }
       __syncthreads();
@@ -360,8 +379,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int v = 4 * v4 + e;
-                        p[v] = __expf(aS[v] * scale - Lv[e]);
-                        ds[v] = p[v] * (aP[v] - Dv[e]) * scale;
+                        p[v] = __builtin_amdgcn_exp2f(aS[v] * c2 - Lv[e]);
+                        ds[v] = p[v] * (aP[v] - Dv[e]);          // 1/sqrt(head_dim) applied to the finished dK
                     }
                 }
 #pragma unroll
@@ -390,7 +409,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
             for (int v4 = 0; v4 < 4; ++v4) {
                 const int d = dt * 32 + 8 * v4 + 4 * g;
                 if (d < dh) {
-                    store4_bf16(dk + d, accK[dt][4 * v4], accK[dt][4 * v4 + 1], accK[dt][4 * v4 + 2], accK[dt][4 * v4 + 3]);
+                    store4_bf16(dk + d, accK[dt][4 * v4] * scale, accK[dt][4 * v4 + 1] * scale,
+                                accK[dt][4 * v4 + 2] * scale, accK[dt][4 * v4 + 3] * scale);
                     store4_bf16(dv + d, accV[dt][4 * v4], accV[dt][4 * v4 + 1], accV[dt][4 * v4 + 2], accV[dt][4 * v4 + 3]);
                 }
             }
