@@ -39,54 +39,69 @@ __device__ __forceinline__ void store4(bf16* p, f4 v) {
 }
 
 // ---- LayerNorm forward -----------------------------------------------------------
-// Lane l of the row's wavefront holds 4-element chunks l, l+64, ... (MAXJ of them).
+// Lane l of the row's wavefront holds 4-element chunks l, l+64, ... (MAXJ of them).  A wavefront
+// handles two rows (rows w and w + M/2-ish apart are both requested before either is reduced), so
+// every lane has two independent memory round trips in flight.
 template <typename TA, typename TP, int MAXJ>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const float* __restrict__ x, const TP* __restrict__ g,
                                                      const TP* __restrict__ b, float eps,
                                                      TA* __restrict__ y, float* __restrict__ stats,
                                                      int M, int D) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + wave;
-    if (row >= M) return;
+    const int half = (M + 1) >> 1;
+    const int r0 = blockIdx.x * 4 + wave;          // rows r0 and r0 + half
+    if (r0 >= half) return;
     const int nch = D >> 2;
-    const float* xr = x + (int64_t)row * D;
-    f4 v[MAXJ];
-    float s = 0.f;
+    int rows[2] = {r0, r0 + half};
+    const bool live1 = rows[1] < M;
+    f4 v[2][MAXJ];
 #pragma unroll
-    for (int j = 0; j < MAXJ; ++j) {
-        int c = lane + 64 * j;
-        if (c < nch) {
-            v[j] = load4(xr + 4 * c);
-            s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+    for (int k = 0; k < 2; ++k) {
+        const float* xr = x + (int64_t)rows[k] * D;
+        if (k == 1 && !live1) break;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            int c = lane + 64 * j;
+            if (c < nch) v[k][j] = load4(xr + 4 * c);
         }
     }
-    const float mean = wave_sum(s) / (float)D;
-    float q = 0.f;
 #pragma unroll
-    for (int j = 0; j < MAXJ; ++j) {
-        int c = lane + 64 * j;
-        if (c < nch) {
-            float a0 = v[j].x - mean, a1 = v[j].y - mean, a2 = v[j].z - mean, a3 = v[j].w - mean;
-            q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
-        }
-    }
-    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)D + eps);
-    TA* yr = y + (int64_t)row * D;
+    for (int k = 0; k < 2; ++k) {
+        if (k == 1 && !live1) break;
+        float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < MAXJ; ++j) {
-        int c = lane + 64 * j;
-        if (c < nch) {
-            f4 gg = load4(g + 4 * c), bb = load4(b + 4 * c), o;
-            o.x = (v[j].x - mean) * rstd * gg.x + bb.x;
-            o.y = (v[j].y - mean) * rstd * gg.y + bb.y;
-            o.z = (v[j].z - mean) * rstd * gg.z + bb.z;
-            o.w = (v[j].w - mean) * rstd * gg.w + bb.w;
-            store4(yr + 4 * c, o);
+        for (int j = 0; j < MAXJ; ++j) {
+            int c = lane + 64 * j;
+            if (c < nch) s += (v[k][j].x + v[k][j].y) + (v[k][j].z + v[k][j].w);
         }
-    }
-    if (lane == 0) {
-        stats[2 * (int64_t)row] = mean;
-        stats[2 * (int64_t)row + 1] = rstd;
+        const float mean = wave_sum(s) / (float)D;
+        float q = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            int c = lane + 64 * j;
+            if (c < nch) {
+                float a0 = v[k][j].x - mean, a1 = v[k][j].y - mean, a2 = v[k][j].z - mean, a3 = v[k][j].w - mean;
+                q += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+            }
+        }
+        const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)D + eps);
+        TA* yr = y + (int64_t)rows[k] * D;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            int c = lane + 64 * j;
+            if (c < nch) {
+                f4 gg = load4(g + 4 * c), bb = load4(b + 4 * c), o;
+                o.x = (v[k][j].x - mean) * rstd * gg.x + bb.x;
+                o.y = (v[k][j].y - mean) * rstd * gg.y + bb.y;
+                o.z = (v[k][j].z - mean) * rstd * gg.z + bb.z;
+                o.w = (v[k][j].w - mean) * rstd * gg.w + bb.w;
+                store4(yr + 4 * c, o);
+            }
+        }
+        if (lane == 0) {
+            stats[2 * (int64_t)rows[k]] = mean;
+            stats[2 * (int64_t)rows[k] + 1] = rstd;
+        }
     }
 }
 
@@ -101,7 +116,7 @@ template <typename TA, typename TP>
 int ln_forward(hipStream_t s, const float* x, const TP* g, const TP* b, float eps,
                TA* y, float* stats, int M, int D) {
     ProfScope ps(K_LN_FWD, s, (double)M * D * (4 + sizeof(TA)));
-    dim3 grid((M + 3) / 4), block(256);
+    dim3 grid(((M + 1) / 2 + 3) / 4), block(256);
     switch (pick_maxj(D)) {
 #define CASE(J) case J: hipLaunchKernelGGL((ln_fwd_kernel<TA, TP, J>), grid, block, 0, s, x, g, b, eps, y, stats, M, D); break;
         CASE(2) CASE(4) CASE(8) CASE(16) CASE(32)
@@ -146,8 +161,14 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
     for (int row = row0 + wave; row < row1; row += 4) {
         const float mean = stats[2 * (int64_t)row], rstd = stats[2 * (int64_t)row + 1];
         const int64_t base = (int64_t)row * D;
-        f4 xh[MAXJ], dh[MAXJ];
+        f4 xh[MAXJ], dh[MAXJ], rv[MAXJ];
         float c1 = 0.f, c2 = 0.f;
+        // all three input rows are requested up front: one memory round trip per row, not two
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            int c = lane + 64 * j;
+            if (c < nch) rv[j] = load4(r + base + 4 * c);
+        }
 #pragma unroll
         for (int j = 0; j < MAXJ; ++j) {
             int c = lane + 64 * j;
@@ -168,11 +189,11 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
         for (int j = 0; j < MAXJ; ++j) {
             int c = lane + 64 * j;
             if (c < nch) {
-                f4 rv = load4(r + base + 4 * c), o;
-                o.x = rv.x + rstd * (dh[j].x - c1 - xh[j].x * c2);
-                o.y = rv.y + rstd * (dh[j].y - c1 - xh[j].y * c2);
-                o.z = rv.z + rstd * (dh[j].z - c1 - xh[j].z * c2);
-                o.w = rv.w + rstd * (dh[j].w - c1 - xh[j].w * c2);
+                f4 o;
+                o.x = rv[j].x + rstd * (dh[j].x - c1 - xh[j].x * c2);
+                o.y = rv[j].y + rstd * (dh[j].y - c1 - xh[j].y * c2);
+                o.z = rv[j].z + rstd * (dh[j].z - c1 - xh[j].z * c2);
+                o.w = rv[j].w + rstd * (dh[j].w - c1 - xh[j].w * c2);
                 ao[j].x += o.x; ao[j].y += o.y; ao[j].z += o.z; ao[j].w += o.w;
                 store4(out + base + 4 * c, o);
                 if (outb) store4(outb + base + 4 * c, o);
