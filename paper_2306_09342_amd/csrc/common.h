@@ -84,6 +84,20 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
     return cdf + x * pdf;
 }
 
+// One fixed-order column reduction, described so that several of them can share a launch:
+// out[i] = sum over p = 0..P-1 (ascending) of partial[p * stride + i] for i < n; elements [0, split) go to
+// `out`, elements [split, n) to `out2` (dropped if out2 is null).
+struct RedSeg {
+    const float* partial;
+    float* out;
+    float* out2;
+    int64_t stride, n, split;
+    int P;
+};
+constexpr int RED_MAX_SEGS = 6;
+// All segments in one launch (every length a multiple of 4, nseg <= RED_MAX_SEGS).
+int reduce_multi(hipStream_t s, const RedSeg* segs, int nseg);
+
 // ---- epilogue description shared by the GEMM launchers ----------------------------
 enum EpiKind {
     EPI_BIAS = 0,      // out = acc + bias[n]                               (out: act type)
@@ -129,9 +143,9 @@ int gemm_nn_f32(hipStream_t s, const float* A, int64_t lda, const float* B, int6
 // dW[N,K] (float32, ld = K) = G[M,N]^T * A[M,K]  -- reduction over the M tokens.
 // `partial` is scratch for the fixed-order split of the reduction (may be unused).
 int gemm_wgrad_f32(hipStream_t s, const float* G, int64_t ldg, const float* A, int64_t lda,
-                   int M, int N, int K, float* dW, float* partial, int64_t partial_elems);
+                   int M, int N, int K, float* dW, float* partial, int64_t partial_elems, RedSeg* defer = nullptr);
 int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
-                    int M, int N, int K, float* dW, float* partial, int64_t partial_elems);
+                    int M, int N, int K, float* dW, float* partial, int64_t partial_elems, RedSeg* defer = nullptr);
 
 // plain vector-ALU flavours (also the fall-back for shapes the matrix-core kernels do not take)
 int gemm_nt_bf16_simple(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
@@ -155,12 +169,13 @@ int ln_forward(hipStream_t s, const float* x, const TP* g, const TP* b, float ep
 template <typename TA, typename TP>
 int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats, const TP* g,
                 const float* r, float* out, TA* outb, float* dgb, float* dbias,
-                float* partial, int M, int D);
+                float* partial, int M, int D, RedSeg* defer = nullptr);
 int64_t ln_bwd_partial_elems(int M, int D);
 
-// out[n] = sum_m in[m, n]   (float32 out, fixed summation order)
+// out[n] = sum_m in[m, n]   (float32 out, fixed summation order).  With `defer` the second stage is not
+// launched: its description is returned for a later reduce_multi.
 template <typename T>
-int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, float* partial);
+int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, float* partial, RedSeg* defer = nullptr);
 int64_t colsum_partial_elems(int M, int N);
 
 // out[i] = sum_p partial[p * stride + i], p ascending

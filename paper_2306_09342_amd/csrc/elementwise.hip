@@ -235,43 +235,70 @@ __device__ __forceinline__ void reduce_store(float* out, float* out2, int64_t sp
     else if (out2) *reinterpret_cast<float4*>(out2 + 4 * (i - split4)) = acc;
 }
 
-__global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ partial, int P,
-                                                          int64_t stride, int64_t n4, float* __restrict__ out,
-                                                          float* __restrict__ out2, int64_t split4) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n4) return;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int p = 0; p < P; ++p) {
-        float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * stride + 4 * i);
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+// ---- several fixed-order reductions in one launch ----------------------------------------------------
+struct RedSegDev { const float* partial; float* out; float* out2; int64_t stride, n4, split4; int P, first_block; };
+struct RedArgs { RedSegDev seg[RED_MAX_SEGS]; int nseg; };
+
+// Segments with many partial rows (P > 32) use 16 row-lanes per group of 16 column quads, folded in
+// lane order through LDS; the others one thread per column quad.  Either way the order is fixed.
+__global__ __launch_bounds__(256) void reduce_multi_kernel(RedArgs a) {
+    __shared__ float4 sh[256];
+    int si = 0;
+#pragma unroll
+    for (int k = 1; k < RED_MAX_SEGS; ++k)
+        if (k < a.nseg && (int)blockIdx.x >= a.seg[k].first_block) si = k;
+    const RedSegDev g = a.seg[si];
+    const int lb = blockIdx.x - g.first_block;
+    if (g.P > 32) {
+        const int cg = threadIdx.x & 15, pl = threadIdx.x >> 4;
+        const int64_t i = (int64_t)lb * 16 + cg;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < g.n4) {
+            for (int p = pl; p < g.P; p += 16) {
+                float4 v = *reinterpret_cast<const float4*>(g.partial + (int64_t)p * g.stride + 4 * i);
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+        }
+        sh[threadIdx.x] = acc;
+        __syncthreads();
+        if (pl == 0 && i < g.n4) {
+            for (int q = 1; q < 16; ++q) {
+                float4 v = sh[q * 16 + cg];
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            reduce_store(g.out, g.out2, g.split4, i, acc);
+        }
+    } else {
+        const int64_t i = (int64_t)lb * 256 + threadIdx.x;
+        if (i >= g.n4) return;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int p = 0; p < g.P; ++p) {
+            float4 v = *reinterpret_cast<const float4*>(g.partial + (int64_t)p * g.stride + 4 * i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        reduce_store(g.out, g.out2, g.split4, i, acc);
     }
-    reduce_store(out, out2, split4, i, acc);
 }
 
-// Same sum for many partial rows: 16 row-lanes per column group walk the rows
-// p = lane, lane+16, ... and are folded in lane order through LDS.
-__global__ __launch_bounds__(256) void reduce_rows_wide_kernel(const float* __restrict__ partial, int P,
-                                                               int64_t stride, int64_t n4, float* __restrict__ out,
-                                                               float* __restrict__ out2, int64_t split4) {
-    __shared__ float4 sh[256];
-    const int cg = threadIdx.x & 15, pl = threadIdx.x >> 4;
-    const int64_t i = (int64_t)blockIdx.x * 16 + cg;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n4) {
-        for (int p = pl; p < P; p += 16) {
-            float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)p * stride + 4 * i);
-            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-        }
+int reduce_multi(hipStream_t s, const RedSeg* segs, int nseg) {
+    if (nseg <= 0) return REV_OK;
+    if (nseg > RED_MAX_SEGS) { set_error("reduce_multi: too many segments"); return REV_EINVAL; }
+    RedArgs a;
+    a.nseg = nseg;
+    int blocks = 0;
+    double bytes = 0;
+    for (int k = 0; k < nseg; ++k) {
+        const RedSeg& g = segs[k];
+        if (g.n % 4 != 0 || g.split % 4 != 0) { set_error("reduce_multi: lengths must be multiples of 4"); return REV_EINVAL; }
+        const int64_t n4 = g.n / 4;
+        a.seg[k] = {g.partial, g.out, g.out2, g.stride, n4, g.split / 4, g.P, blocks};
+        blocks += (int)(g.P > 32 ? (n4 + 15) / 16 : (n4 + 255) / 256);
+        bytes += (double)(g.P + 1) * g.n * 4;
     }
-    sh[threadIdx.x] = acc;
-    __syncthreads();
-    if (pl == 0 && i < n4) {
-        for (int q = 1; q < 16; ++q) {
-            float4 v = sh[q * 16 + cg];
-            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-        }
-        reduce_store(out, out2, split4, i, acc);
-    }
+    ProfScope ps(K_REDUCE, s, bytes);
+    hipLaunchKernelGGL(reduce_multi_kernel, dim3(blocks), dim3(256), 0, s, a);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
 }
 
 int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out) {
@@ -281,19 +308,8 @@ int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int6
 // Elements [0, split) of the sum go to out, elements [split, n) to out2 (dropped if out2 is null).
 int reduce_rows2(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out, float* out2,
                  int64_t split) {
-    if (n % 4 != 0 || split % 4 != 0) { set_error("reduce_rows: lengths must be multiples of 4"); return REV_EINVAL; }
-    const int64_t split4 = split / 4;
-    ProfScope ps(K_REDUCE, s, (double)(P + 1) * n * 4);
-    int64_t n4 = n / 4;
-    if (P > 32) {
-        hipLaunchKernelGGL(reduce_rows_wide_kernel, dim3((unsigned)((n4 + 15) / 16)), dim3(256), 0, s, partial, P,
-                           stride, n4, out, out2, split4);
-    } else {
-        hipLaunchKernelGGL(reduce_rows_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, partial, P,
-                           stride, n4, out, out2, split4);
-    }
-    REV_HIP(hipGetLastError());
-    return REV_OK;
+    const RedSeg g = {partial, out, out2, stride, n, split, P};
+    return reduce_multi(s, &g, 1);
 }
 
 int64_t ln_bwd_partial_elems(int M, int D) {
@@ -303,7 +319,7 @@ int64_t ln_bwd_partial_elems(int M, int D) {
 template <typename TA, typename TP>
 int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats, const TP* g,
                 const float* r, float* out, TA* outb, float* dgb, float* dbias,
-                float* partial, int M, int D) {
+                float* partial, int M, int D, RedSeg* defer) {
     const int nblk = (M + LNB_ROWS - 1) / LNB_ROWS;
     {
         ProfScope ps(K_LN_BWD, s, (double)M * D * (sizeof(TA) + 4 + 4 + 4 + (outb ? sizeof(TA) : 0)));
@@ -326,10 +342,12 @@ int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats,
         REV_HIP(hipGetLastError());
     }
     // partial rows are [dgamma(D) | dbeta(D) | colsum(out)(D)]; gamma and beta gradients are adjacent in dgb
-    return reduce_rows2(s, partial, nblk, 3 * (int64_t)D, 3 * (int64_t)D, dgb, dbias, 2 * (int64_t)D);
+    const RedSeg seg = {partial, dgb, dbias, 3 * (int64_t)D, 3 * (int64_t)D, 2 * (int64_t)D, nblk};
+    if (defer) { *defer = seg; return REV_OK; }
+    return reduce_multi(s, &seg, 1);
 }
-template int ln_backward<float, float>(hipStream_t, const float*, const float*, const float*, const float*, const float*, float*, float*, float*, float*, float*, int, int);
-template int ln_backward<bf16, bf16>(hipStream_t, const bf16*, const float*, const float*, const bf16*, const float*, float*, bf16*, float*, float*, float*, int, int);
+template int ln_backward<float, float>(hipStream_t, const float*, const float*, const float*, const float*, const float*, float*, float*, float*, float*, float*, int, int, RedSeg*);
+template int ln_backward<bf16, bf16>(hipStream_t, const bf16*, const float*, const float*, const bf16*, const float*, float*, bf16*, float*, float*, float*, int, int, RedSeg*);
 
 // ---- column sums (bias gradients) --------------------------------------------------------
 // grid (column tiles of 256, row chunks); each wavefront sums a quarter of the
@@ -370,7 +388,7 @@ static int colsum_chunks(int M, int N) {
 int64_t colsum_partial_elems(int M, int N) { return (int64_t)colsum_chunks(M, N) * N; }
 
 template <typename T>
-int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, float* partial) {
+int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, float* partial, RedSeg* defer) {
     int P = colsum_chunks(M, N);
     int rpb = (M + P - 1) / P;
     P = (M + rpb - 1) / rpb;
@@ -380,10 +398,12 @@ int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, flo
         hipLaunchKernelGGL((colsum_kernel<T>), grid, block, 0, s, in, ld, M, N, rpb, partial);
         REV_HIP(hipGetLastError());
     }
-    return reduce_rows(s, partial, P, N, N, out);
+    const RedSeg g = {partial, out, nullptr, (int64_t)N, (int64_t)N, (int64_t)N, P};
+    if (defer) { *defer = g; return REV_OK; }
+    return reduce_multi(s, &g, 1);
 }
-template int colsum<float>(hipStream_t, const float*, int64_t, int, int, float*, float*);
-template int colsum<bf16>(hipStream_t, const bf16*, int64_t, int, int, float*, float*);
+template int colsum<float>(hipStream_t, const float*, int64_t, int, int, float*, float*, RedSeg*);
+template int colsum<bf16>(hipStream_t, const bf16*, int64_t, int, int, float*, float*, RedSeg*);
 
 // ---- conversion, copy, transpose ------------------------------------------------------------
 __global__ __launch_bounds__(256) void cvt_kernel(const float* __restrict__ in, bf16* __restrict__ out, int64_t n4) {

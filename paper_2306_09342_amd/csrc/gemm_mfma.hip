@@ -319,7 +319,8 @@ int launch_wgrad_dma(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, i
 int g_wg_variant = 1;   // tuning hook: 0 = register-staged kernel, 1 = direct-to-LDS kernel
 
 int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
-                    int M, int N, int K, float* dW, float* partial, int64_t partial_elems) {
+                    int M, int N, int K, float* dW, float* partial, int64_t partial_elems, RedSeg* defer) {
+    if (defer) defer->P = 0;            // P == 0: nothing left to reduce
     if ((ldg & 7) || (lda & 7) || (N & 7) || (K & 7) || ((uintptr_t)G & 15) || ((uintptr_t)A & 15)) {
         return gemm_wgrad_bf16_simple(s, G, ldg, A, lda, M, N, K, dW);
     }
@@ -347,7 +348,11 @@ int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, in
                            S > 1 ? partial : dW, (int64_t)N * K);
         REV_HIP(hipGetLastError());
     }
-    if (S > 1) return reduce_rows(s, partial, S, (int64_t)N * K, (int64_t)N * K, dW);
+    if (S > 1) {
+        const RedSeg g = {partial, dW, nullptr, (int64_t)N * K, (int64_t)N * K, (int64_t)N * K, S};
+        if (defer) { *defer = g; return REV_OK; }
+        return reduce_multi(s, &g, 1);
+    }
     return REV_OK;
 }
 

@@ -105,9 +105,9 @@ struct Layout {
     int64_t gy1b[2];       // act-typed copy of gY1 (bf16 mode), by block parity
     int64_t dh[2], dqkv[2]; // by block parity: read by the weight-gradient kernels of the block
     int64_t dn, dO, delta;
-    int64_t part_ln, part_col, part_wg;
+    int64_t part_ln[2], part_col[2], part_wg[4];   // one per deferred reduction of a block
     int64_t total;
-    int64_t part_wg_elems;
+    int64_t part_wg_elems[4];
 };
 
 static Layout make_layout(const rev_cfg& c) {
@@ -149,27 +149,27 @@ static Layout make_layout(const rev_cfg& c) {
     L.dn = take(M * D * es);
     L.dO = take(M * D * es);
     L.delta = take((int64_t)c.batch * c.n_heads * c.seq_len * 4);
-    L.part_ln = take(ln_bwd_partial_elems((int)M, (int)D) * 4);
+    L.part_ln[0] = take(ln_bwd_partial_elems((int)M, (int)D) * 4);
+    L.part_ln[1] = take(ln_bwd_partial_elems((int)M, (int)D) * 4);
     {
-        int64_t e = colsum_partial_elems((int)M, (int)D);
-        int64_t e2 = colsum_partial_elems((int)M, (int)Dm);
-        int64_t e3 = colsum_partial_elems((int)M, (int)(3 * D));
-        int64_t e4 = (int64_t)gemm_colsum_strips_max((int)M) * Dm;     // fused bias-gradient strips
-        if (e2 > e) e = e2;
-        if (e3 > e) e = e3;
-        if (e4 > e) e = e4;
-        L.part_col = take(e * 4);
+        // [0]: fc1 bias gradient (column-sum strips of the GELU' epilogue, or a plain column sum);
+        // [1]: QKV bias gradient; also the top block's fc2 bias gradient
+        int64_t e0 = colsum_partial_elems((int)M, (int)Dm);
+        int64_t e0b = (int64_t)gemm_colsum_strips_max((int)M) * Dm;
+        if (e0b > e0) e0 = e0b;
+        int64_t e1 = colsum_partial_elems((int)M, (int)(3 * D));
+        int64_t e1b = colsum_partial_elems((int)M, (int)D);
+        if (e1b > e1) e1 = e1b;
+        L.part_col[0] = take(e0 * 4);
+        L.part_col[1] = take(e1 * 4);
     }
     if (c.mode == REV_MODE_BF16) {
-        int64_t e = wgrad_partial_elems((int)M, (int)D, (int)Dm);
-        int64_t e2 = wgrad_partial_elems((int)M, (int)Dm, (int)D);
-        int64_t e3 = wgrad_partial_elems((int)M, (int)D, (int)D);
-        int64_t e4 = wgrad_partial_elems((int)M, (int)(3 * D), (int)D);
-        if (e2 > e) e = e2;
-        if (e3 > e) e = e3;
-        if (e4 > e) e = e4;
-        L.part_wg_elems = e;
-        L.part_wg = take(e * 4);
+        // split-reduction scratch of the four weight gradients: fc2, fc1, proj, qkv
+        const int64_t nn[4] = {D, Dm, D, 3 * D}, kk[4] = {Dm, D, D, D};
+        for (int w = 0; w < 4; ++w) {
+            L.part_wg_elems[w] = wgrad_partial_elems((int)M, (int)nn[w], (int)kk[w]);
+            L.part_wg[w] = take((L.part_wg_elems[w] > 0 ? L.part_wg_elems[w] : 64) * 4);
+        }
     }
     L.total = off;
     return L;
@@ -202,8 +202,8 @@ template <> struct Ops<float> {
         return gemm_nt_f32(s, A, lda, B, ldb, M, N, K, e);
     }
     static int wgrad(hipStream_t s, const float* G, int64_t ldg, const float* A, int64_t lda, int M, int N, int K,
-                     float* dW, float* part, int64_t pe) {
-        return gemm_wgrad_f32(s, G, ldg, A, lda, M, N, K, dW, part, pe);
+                     float* dW, float* part, int64_t pe, RedSeg* defer) {
+        return gemm_wgrad_f32(s, G, ldg, A, lda, M, N, K, dW, part, pe, defer);
     }
 };
 template <> struct Ops<bf16> {
@@ -211,8 +211,8 @@ template <> struct Ops<bf16> {
         return gemm_nt_bf16(s, A, lda, B, ldb, M, N, K, e);
     }
     static int wgrad(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,
-                     float* dW, float* part, int64_t pe) {
-        return gemm_wgrad_bf16(s, G, ldg, A, lda, M, N, K, dW, part, pe);
+                     float* dW, float* part, int64_t pe, RedSeg* defer) {
+        return gemm_wgrad_bf16(s, G, ldg, A, lda, M, N, K, dW, part, pe, defer);
     }
 };
 
@@ -305,25 +305,28 @@ struct Runner {
         T* dqkv = at<T>(L.dqkv[blk & 1]);
         T* dn = at<T>(L.dn);
         T* dO = at<T>(L.dO);
-        float* pcol = at<float>(L.part_col);
-        float* pln = at<float>(L.part_ln);
+        float* pcol0 = at<float>(L.part_col[0]);
+        float* pcol1 = at<float>(L.part_col[1]);
         T* gy1b = gy1_act(blk, o1);
+        // second stages of the block's fixed-order sums are gathered and run as one launch at the end
+        RedSeg segs[4];
+        int nseg = 0;
 
         // ---- G branch: dh = (dY2 W2) * gelu'(h); the bias gradient of fc1 (column sums of dh) rides
         // in the epilogue of the matrix-core kernel, otherwise it is a separate pass
         Epi e = {}; e.kind = EPI_GELU_BWD; e.out = dhb; e.aux = sl.h; e.ldo = Dm;
         bool fused_db1 = false;
         if constexpr (kBf16) fused_db1 = gemm_bf16_fast_path(d2b, D, P(blk, T_WFC2), Dm, Dm, D, e);
-        if (fused_db1) e.colsum = pcol;
+        if (fused_db1) e.colsum = pcol0;
         RC(dgrad(s, blk, T_WFC2, d2b, D, Dm, e));
         if (ev) REV_HIP(hipEventRecord(ev[0], s));
-        if (fused_db1) RC(reduce_rows(s, pcol, gemm_colsum_strips(M), Dm, Dm, G(blk, T_BFC1)));
-        else RC(colsum<T>(s, dhb, Dm, M, Dm, G(blk, T_BFC1), pcol));
+        if (fused_db1) segs[nseg++] = {pcol0, G(blk, T_BFC1), nullptr, (int64_t)Dm, (int64_t)Dm, (int64_t)Dm, gemm_colsum_strips(M)};
+        else RC(colsum<T>(s, dhb, Dm, M, Dm, G(blk, T_BFC1), pcol0, &segs[nseg++]));
         Epi p = {}; p.kind = EPI_PLAIN; p.out = dn; p.ldo = D;
         RC(dgrad(s, blk, T_WFC1, dhb, Dm, D, p));
         // gY1 = dY1 + LN2bwd(dn); its column sums are the bias gradient of the projection
         RC((ln_backward<T, T>(s, dn, y1, sl.st2, P(blk, T_LN2G), d1, o1, kBf16 ? gy1b : nullptr,
-                              G(blk, T_LN2G), G(blk, T_BPROJ), pln, M, D)));
+                              G(blk, T_LN2G), G(blk, T_BPROJ), at<float>(L.part_ln[0]), M, D, &segs[nseg++])));
         if (ev) REV_HIP(hipEventRecord(ev[1], s));
         // ---- F branch
         Epi q = {}; q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
@@ -332,12 +335,13 @@ struct Runner {
         if (ev) REV_HIP(hipEventRecord(ev[2], s));
         Epi r = {}; r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
         RC(dgrad(s, blk, T_WQKV, dqkv, 3 * D, D, r));
-        RC(colsum<T>(s, dqkv, 3 * D, M, 3 * D, G(blk, T_BQKV), pcol));
+        RC(colsum<T>(s, dqkv, 3 * D, M, 3 * D, G(blk, T_BQKV), pcol1, &segs[nseg++]));
         // dX2 = dY2 + LN1bwd(dn); dX2 is the block below's dY2, so its column sums are that block's
         // fc2 bias gradient
         RC((ln_backward<T, T>(s, dn, x2, sl.st1, P(blk, T_LN1G), d2, o2, kBf16 ? o2b : nullptr,
-                              G(blk, T_LN1G), blk > 0 ? G(blk - 1, T_BFC2) : nullptr, pln, M, D)));
-        return REV_OK;
+                              G(blk, T_LN1G), blk > 0 ? G(blk - 1, T_BFC2) : nullptr, at<float>(L.part_ln[1]), M, D,
+                              &segs[nseg++])));
+        return reduce_multi(s, segs, nseg);
     }
 
     // ev (nullable): events to wait for on s before the kernels that read dY2 copy / dh / gY1 / dqkv
@@ -346,18 +350,25 @@ struct Runner {
         Slot sl = slot(blk);
         T* dhb = at<T>(L.dh[blk & 1]);
         T* dqkv = at<T>(L.dqkv[blk & 1]);
-        float* pwg = kBf16 ? at<float>(L.part_wg) : nullptr;
+        float* pwg[4] = {nullptr, nullptr, nullptr, nullptr};
+        if constexpr (kBf16) for (int w = 0; w < 4; ++w) pwg[w] = at<float>(L.part_wg[w]);
         T* gy1b = gy1_act(blk, o1);
+        RedSeg segs[4];
         if (ev) REV_HIP(hipStreamWaitEvent(s, ev[0], 0));
-        RC(Ops<T>::wgrad(s, d2b, D, sl.a, Dm, M, D, Dm, G(blk, T_WFC2), pwg, L.part_wg_elems));
+        RC(Ops<T>::wgrad(s, d2b, D, sl.a, Dm, M, D, Dm, G(blk, T_WFC2), pwg[0], L.part_wg_elems[0], &segs[0]));
         if (done_w2) REV_HIP(hipEventRecord(done_w2, s));
         if (ev) REV_HIP(hipStreamWaitEvent(s, ev[1], 0));
-        RC(Ops<T>::wgrad(s, dhb, Dm, sl.n2, D, M, Dm, D, G(blk, T_WFC1), pwg, L.part_wg_elems));
+        RC(Ops<T>::wgrad(s, dhb, Dm, sl.n2, D, M, Dm, D, G(blk, T_WFC1), pwg[1], L.part_wg_elems[1], &segs[1]));
         if (ev) REV_HIP(hipStreamWaitEvent(s, ev[2], 0));
-        RC(Ops<T>::wgrad(s, gy1b, D, sl.o, D, M, D, D, G(blk, T_WPROJ), pwg, L.part_wg_elems));
+        RC(Ops<T>::wgrad(s, gy1b, D, sl.o, D, M, D, D, G(blk, T_WPROJ), pwg[2], L.part_wg_elems[2], &segs[2]));
         if (ev) REV_HIP(hipStreamWaitEvent(s, ev[3], 0));
-        RC(Ops<T>::wgrad(s, dqkv, 3 * D, sl.n1, D, M, 3 * D, D, G(blk, T_WQKV), pwg, L.part_wg_elems));
-        return REV_OK;
+        RC(Ops<T>::wgrad(s, dqkv, 3 * D, sl.n1, D, M, 3 * D, D, G(blk, T_WQKV), pwg[3], L.part_wg_elems[3], &segs[3]));
+        // one launch for the split reductions of all four
+        RedSeg live[4];
+        int nseg = 0;
+        for (int w = 0; w < 4; ++w)
+            if (segs[w].P > 0) live[nseg++] = segs[w];
+        return reduce_multi(s, live, nseg);
     }
 
     // residual level `lvl` (0..N): stream s1/s2 pointers
@@ -399,7 +410,7 @@ struct Runner {
         if (doV) {
             // fc2 bias gradient of the top block: column sums of the incoming dY2 (lower blocks get
             // theirs from the LayerNorm-backward kernel that produces their dY2)
-            RC(colsum<float>(sv, dY2, D, M, D, G(N - 1, T_BFC2), at<float>(L.part_col)));
+            RC(colsum<float>(sv, dY2, D, M, D, G(N - 1, T_BFC2), at<float>(L.part_col[1])));
             if constexpr (kBf16) {
                 T* b = at<T>(L.cot2b[N & 1]);
                 RC(convert_f32_to_bf16(sv, dY2, b, (int64_t)M * D));
