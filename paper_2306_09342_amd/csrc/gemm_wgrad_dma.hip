@@ -31,8 +31,15 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
     const int tiles_q = (K + WD_BQ - 1) / WD_BQ;
     const int tiles = ((N + WD_BP - 1) / WD_BP) * tiles_q;
     const int split = blockIdx.x / tiles;
+    // Each XCD takes one contiguous run of tiles.  The slow tile index is the one along the WIDER
+    // output dimension, so the bigger operand is partitioned over the XCDs' L2s and only the smaller
+    // one is fetched by all of them.
     const int tile = xcd_remap(blockIdx.x % tiles, tiles);
-    const int p0 = (tile / tiles_q) * WD_BP, q0 = (tile % tiles_q) * WD_BQ;
+    const int tiles_p = tiles / tiles_q;
+    int tp, tq;
+    if (K > N) { tq = tile / tiles_p; tp = tile - tq * tiles_p; }
+    else { tp = tile / tiles_q; tq = tile - tp * tiles_q; }
+    const int p0 = tp * WD_BP, q0 = tq * WD_BQ;
     const int total_steps = (M + WD_BR - 1) / WD_BR;
     const int step0 = split * steps_per_split;
     const int nsteps = max(0, min(steps_per_split, total_steps - step0));
