@@ -1,16 +1,14 @@
-// bf16 matrix-core GEMMs for gfx950 (v_mfma_f32_32x32x16_bf16, float32 accumulate).
+// bf16 matrix-core GEMM entry points and the register-staged NT kernel.
 //
-//  gemm_nt   C[M,N] = A[M,K] * B[N,K]^T      both operands contraction-contiguous;
-//            LDS tiles keep the global layout, fragments are 16-byte LDS reads.
-//  wgrad     dW[N,K] = G[M,N]^T * A[M,K]     both operands have the contraction
-//            index (the token) as the slow one; tiles are stored in LDS as they
-//            come from HBM and fragments are read with the LDS transpose read
-//            (ds_read_b64_tr_b16), so no operand is ever transposed in memory.
-//            The token reduction is split into a fixed number of ranges whose
-//            partial tiles are summed afterwards in range order: results do not
-//            depend on scheduling.
+//  gemm_nt_bf16 / gemm_nn_bf16   C = A * B^T  /  C = A * B  with fused epilogue.  Problems with
+//            K % 64 == 0 go to the pipelined direct-to-LDS kernel (gemm_nt_dma.hip); other K % 8 == 0
+//            problems to the register-staged kernel below (global -> VGPR -> LDS, padded tiles);
+//            anything else to the plain-ALU kernels.
+//  gemm_wgrad_bf16               dW[N,K] = G[M,N]^T * A[M,K]: picks the number of token ranges and
+//            launches the kernel of gemm_wgrad_dma.hip; the partial tiles of the ranges are summed
+//            afterwards in range order, so results do not depend on scheduling.
 //
-// Register layout of the 32x32x16 instruction, per lane l of the wavefront:
+// Register layout of v_mfma_f32_32x32x16_bf16, per lane l of the wavefront:
 //   A operand: row l%32, k = 8*(l/32) .. +7;  B operand: column l%32, same k;
 //   D: column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for accumulator register v.
 #include "mfma.h"
@@ -204,7 +202,6 @@ int gemm_nt_bf16(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64
 constexpr int WG_BP = 128;            // tile rows (n)
 constexpr int WG_BQ = 128;            // tile cols (k)
 constexpr int WG_BR = 64;             // tokens per step
-constexpr int WG_LDP = 128 + 32;      // LDS pitch in elements (320 B)
 
 // The token reduction is cut into S ranges so that tiles * S fills, but does not exceed, the
 // workgroup slots of the chip (256 CUs x 2 resident workgroups): one full round, no ragged second one.
@@ -222,101 +219,8 @@ int64_t wgrad_partial_elems(int M, int N, int K) {
     return S > 1 ? (int64_t)S * N * K : 0;
 }
 
-__global__ __launch_bounds__(256) void wgrad_kernel(const bf16* __restrict__ G, int64_t ldg,
-                                                    const bf16* __restrict__ A, int64_t lda,
-                                                    int M, int N, int K, int steps_per_split,
-                                                    float* __restrict__ out, int64_t split_stride) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* Gs = reinterpret_cast<uint16_t*>(smem);              // [2][WG_BR][WG_LDP]
-    uint16_t* As = Gs + 2 * WG_BR * WG_LDP;                        // [2][WG_BR][WG_LDP]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wp = wave >> 1, wq = wave & 1;                       // 2 x 2 wavefronts, 64 x 64 each
-    const int tiles_q = (K + WG_BQ - 1) / WG_BQ;
-    const int tiles = ((N + WG_BP - 1) / WG_BP) * tiles_q;
-    const int split = blockIdx.x / tiles;
-    const int tile = xcd_remap(blockIdx.x % tiles, tiles);
-    const int p0 = (tile / tiles_q) * WG_BP, q0 = (tile % tiles_q) * WG_BQ;
-    const int step0 = split * steps_per_split;
-    const int nsteps = min(steps_per_split, (M + WG_BR - 1) / WG_BR - step0);
-
-    f32x16_t acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    // 64 tokens x 16 chunks of 8 columns per operand tile = 1024 chunks, 4 per thread
-    u32x4_t rg[4], ra[4];
-    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-#define WG_GLOAD(st)                                                                                             \
-    {                                                                                                            \
-        const int mbase = (step0 + (st)) * WG_BR;                                                                \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                          \
-            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;                                        \
-            const int m = mbase + row;                                                                           \
-            const int gp = p0 + ch * 8, gq = q0 + ch * 8;                                                        \
-            rg[i] = (m < M && gp < N) ? *reinterpret_cast<const u32x4_t*>(G + (int64_t)m * ldg + gp) : zero4;      \
-            ra[i] = (m < M && gq < K) ? *reinterpret_cast<const u32x4_t*>(A + (int64_t)m * lda + gq) : zero4;      \
-        }                                                                                                        \
-    }
-#define WG_LSTORE(buf)                                                                                           \
-    {                                                                                                            \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                          \
-            const int idx = tid + i * 256, row = idx >> 4, ch = idx & 15;                                        \
-            *reinterpret_cast<u32x4_t*>(Gs + ((buf) * WG_BR + row) * WG_LDP + ch * 8) = rg[i];                     \
-            *reinterpret_cast<u32x4_t*>(As + ((buf) * WG_BR + row) * WG_LDP + ch * 8) = ra[i];                     \
-        }                                                                                                        \
-    }
-
-    if (nsteps > 0) {
-        WG_GLOAD(0);
-        WG_LSTORE(0);
-    }
-    __syncthreads();
-    for (int st = 0; st < nsteps; ++st) {
-        const int buf = st & 1;
-        if (st + 1 < nsteps) WG_GLOAD(st + 1);
-        const uint16_t* Gt = Gs + buf * WG_BR * WG_LDP;
-        const uint16_t* At = As + buf * WG_BR * WG_LDP;
-#pragma unroll
-        for (int kk = 0; kk < WG_BR / 16; ++kk) {
-            bf16x8_t a[2], b[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = tr_frag<8, 4>(Gt, WG_LDP, kk * 16, wp * 64 + i * 32, lane);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = tr_frag<8, 4>(At, WG_LDP, kk * 16, wq * 64 + j * 32, lane);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (st + 1 < nsteps) WG_LSTORE(buf ^ 1);
-        __syncthreads();
-    }
-
-    float* o = out + (int64_t)split * split_stride;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int q = q0 + wq * 64 + j * 32 + (lane & 31);
-        if (q >= K) continue;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int pb = p0 + wp * 64 + i * 32 + 4 * (lane >> 5);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int p = pb + 8 * (v >> 2) + (v & 3);
-                if (p < N) o[(int64_t)p * K + q] = acc[i][j][v];
-            }
-        }
-    }
-}
-
 int launch_wgrad_dma(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,
                      int S, int sps, float* out);
-int g_wg_variant = 1;   // tuning hook: 0 = register-staged kernel, 1 = direct-to-LDS kernel
 
 int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
                     int M, int N, int K, float* dW, float* partial, int64_t partial_elems, RedSeg* defer) {
@@ -332,21 +236,10 @@ int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, in
     const int steps = (M + WG_BR - 1) / WG_BR;
     const int sps = (steps + S - 1) / S;
     const int tiles = ((N + WG_BP - 1) / WG_BP) * ((K + WG_BQ - 1) / WG_BQ);
-    constexpr size_t shmem = (size_t)4 * WG_BR * WG_LDP * sizeof(uint16_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
-        attr_set = true;
-    }
-    if (g_wg_variant == 1) {
+    {
         ProfScope ps(K_GEMM_WGRAD, s, 2.0 * M * N * K);
         int rc = launch_wgrad_dma(s, G, ldg, A, lda, M, N, K, S, sps, S > 1 ? partial : dW);
         if (rc) return rc;
-    } else {
-        ProfScope ps(K_GEMM_WGRAD, s, 2.0 * M * N * K);
-        hipLaunchKernelGGL(wgrad_kernel, dim3(tiles * S), dim3(256), shmem, s, G, ldg, A, lda, M, N, K, sps,
-                           S > 1 ? partial : dW, (int64_t)N * K);
-        REV_HIP(hipGetLastError());
     }
     if (S > 1) {
         const RedSeg g = {partial, dW, nullptr, (int64_t)N * K, (int64_t)N * K, (int64_t)N * K, S};

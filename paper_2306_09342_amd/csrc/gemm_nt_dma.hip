@@ -154,14 +154,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     }
     const int64_t bstep = BKM ? (int64_t)BK * ldb : (int64_t)BK;       // B advance per stage
     const bf16* zero = reinterpret_cast<const bf16*>(g_zero_chunk);
-    auto issue = [&](int kt, int stage) {
+    // loads t0 <= t < t1 of the stage (the whole stage: 0, LPW)
+    auto issue_part = [&](int kt, int stage, int t0, int t1) {
 #pragma unroll
         for (int t = 0; t < LPW; ++t) {
+            if (t < t0 || t >= t1) continue;
             const bool isA = (NW * t) < IA;
             const bf16* p = isA ? src[t] + (int64_t)kt * BK : (src[t] ? src[t] + kt * bstep : zero);
             __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(void, smem + stage * STAGE + dst[t]), 16, 0, 0);
         }
     };
+    auto issue = [&](int kt, int stage) { issue_part(kt, stage, 0, LPW); };
+    // With one wavefront per SIMD the loads of the next stage are handed out in slices between the
+    // product groups of the current one, so the matrix cores start right after the barrier.
+    constexpr bool SPREAD = (NW == 4 && TM * TN >= 16 && NS == 2 && LPW % (BK / 16) == 0);
 
     f32x16_t acc[TN][TM];
 #pragma unroll
@@ -200,7 +206,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __builtin_amdgcn_s_barrier();
 #if !defined(REV_EXP_NOLOAD)
-            if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
+            if (!SPREAD && kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
 #endif
         }
         const unsigned char* st = smem + (kt % NS) * STAGE;
@@ -223,6 +229,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
+#if !defined(REV_EXP_NOLOAD)
+            if (SPREAD && kt + 1 < nk) {
+                constexpr int PER = LPW / (BK / 16);
+                issue_part(kt + 1, (kt + 1) % NS, kk * PER, (kk + 1) * PER);
+            }
+#endif
             __builtin_amdgcn_sched_barrier(0);       // keep the LDS reads ahead of the products that hide them
 #pragma unroll
             for (int j = 0; j < TN; ++j)
