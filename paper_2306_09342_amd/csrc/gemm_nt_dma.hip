@@ -112,7 +112,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     static_assert(NS == 1 || (NS - 2) * LPW < 64, "vmcnt range");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wavefront index as a scalar: LDS destinations of the direct-to-LDS loads (M0) then need no
+    // per-load lane read-out
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int g = lane >> 5;
     // Tile order: column groups of `gn` n-tiles, each group walked over all m-tiles, n fastest inside
@@ -160,7 +163,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         for (int t = 0; t < LPW; ++t) {
             if (t < t0 || t >= t1) continue;
             const bool isA = (NW * t) < IA;
-            const bf16* p = isA ? src[t] + (int64_t)kt * BK : (src[t] ? src[t] + kt * bstep : zero);
+            const bf16* p = isA ? src[t] + (int64_t)kt * BK
+                                : ((!BKM || src[t]) ? src[t] + kt * bstep : zero);   // only K-major B can fall outside
             __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(void, smem + stage * STAGE + dst[t]), 16, 0, 0);
         }
     };

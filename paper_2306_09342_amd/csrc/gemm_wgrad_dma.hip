@@ -26,7 +26,8 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
                                                         int M, int N, int K, int steps_per_split,
                                                         float* __restrict__ out, int64_t split_stride) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: M0 values need no lane read-out
     const int wp = wave >> 1, wq = wave & 1;                       // 2 x 2 wavefronts, 64 x 64 each
     const int tiles_q = (K + WD_BQ - 1) / WD_BQ;
     const int tiles = ((N + WD_BP - 1) / WD_BP) * tiles_q;
