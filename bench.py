@@ -9,6 +9,7 @@ their own, the per-family kernel times and the CPU oracle are reported beside
 it on the same JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vit_b]
+    python bench.py --sweep-batch 1,2,4,8,16,32,64,128,256     # throughput and memory against batch size
 """
 from __future__ import annotations
 
@@ -42,16 +43,170 @@ def algorithmic_flops(cfg):
     return 3 * cfg["n_blocks"] * fwd_unit
 
 
+def memory_model(B, c, cfg):
+    """Workspace bytes of the two reversible schedules as the library sizes them, and what
+    backpropagation with stored activations would need with the same kernels: every block keeps its
+    activation slot and its two output streams instead of one (or two) slots and two (or three)
+    residual levels being reused."""
+    M = cfg["batch"] * cfg["seq_len"]
+    slot = B.rev_stack_slot_bytes(c)
+    level = 2 * M * cfg["d_model"] * 4
+    reprop = B.rev_stack_workspace_bytes_reprop(c)
+    pareprop = B.rev_stack_workspace_bytes(c)
+    N = cfg["n_blocks"]
+    stored = reprop + (N - 1) * slot + max(N - 2, 0) * level
+    return {"reprop_bytes": reprop, "pareprop_bytes": pareprop, "stored_activation_bytes": stored,
+            "slot_bytes": slot, "pareprop_over_reprop": pareprop / reprop, "stored_over_reprop": stored / reprop}
+
+
+def sweep_batch(args, cfg, B, synth, torch, np):
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    batches = [int(b) for b in args.sweep_batch.split(",") if b]
+    flat = synth.make_params(cfg, seed=0)
+    rows = []
+    main_s = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    for b in batches:
+        cb = dict(cfg, batch=b)
+        c = B.make_cfg(**cb)
+        params = torch.from_numpy(flat).cuda().to(B.param_dtype(c))
+        x, dy1, dy2 = synth.make_inputs(cb, seed=0, batch=b)
+        X, dY1, dY2 = (torch.from_numpy(a).cuda() for a in (x, dy1, dy2))
+        ws = B.alloc_workspace(c)
+        Y1, Y2 = B.rev_stack_forward(c, params, X, X, workspace=ws)
+        out = {}
+        out.update(B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws))
+        torch.cuda.synchronize()
+        res = {}
+        for name, fn in (("pareprop", lambda: B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side,
+                                                                             workspace=ws, out=out)),
+                         ("reprop", lambda: B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2,
+                                                                         workspace=ws, out=out))):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            ev = []
+            for _ in range(args.steps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(main_s)
+                fn()
+                e1.record(main_s)
+                ev.append((e0, e1))
+            torch.cuda.synchronize()
+            ms = np.array([a.elapsed_time(z) for a, z in ev])
+            res[name] = {"ms_median": float(np.median(ms)), "ms_mean": float(ms.mean()), "ms_std": float(ms.std()),
+                         "samples_per_s": b / (float(np.median(ms)) * 1e-3)}
+        row = {"batch": b, **res, "pareprop_over_reprop": res["pareprop"]["samples_per_s"] / res["reprop"]["samples_per_s"],
+               "memory": memory_model(B, c, cb)}
+        rows.append(row)
+        print(f"# batch {b}: pareprop {res['pareprop']['samples_per_s']:.1f}/s reprop {res['reprop']['samples_per_s']:.1f}/s "
+              f"x{row['pareprop_over_reprop']:.3f}  ws {row['memory']['pareprop_bytes'] / 2**20:.0f} / "
+              f"{row['memory']['reprop_bytes'] / 2**20:.0f} MiB, stored {row['memory']['stored_activation_bytes'] / 2**20:.0f} MiB",
+              file=sys.stderr, flush=True)
+        del ws, X, dY1, dY2, Y1, Y2, out, params
+        torch.cuda.empty_cache()
+    best = max(rows, key=lambda r: r["pareprop"]["samples_per_s"])
+    print(json.dumps({"metric": f"reversible backward samples/s against batch size, {args.workload}",
+                      "value": best["pareprop"]["samples_per_s"], "unit": "samples/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": best["pareprop"]["ms_median"],
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["mode"],
+                      "data": "synthetic",
+                      "config": {"workload": f"{args.workload}, batch sweep", "best_batch": best["batch"]},
+                      "sweep": rows}))
+
+
+def bench_hierarchy(args, hier, B, synth, torch, np):
+    """Hierarchical (window-attention shaped) workload: one step is the reversible backward pass of
+    every stage, last stage first, each stage a homogeneous stack over its attention windows."""
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    main_s = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    stages = []
+    for si, cfg in enumerate(hier["stages"]):
+        c = B.make_cfg(**cfg)
+        params = torch.from_numpy(synth.make_params(cfg, seed=si)).cuda().to(B.param_dtype(c))
+        x, dy1, dy2 = synth.make_inputs(cfg, seed=si)
+        X, dY1, dY2 = (torch.from_numpy(a).cuda() for a in (x, dy1, dy2))
+        ws = B.alloc_workspace(c)
+        Y1, Y2 = B.rev_stack_forward(c, params, X, X, workspace=ws)
+        out = {}
+        out.update(B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws))
+        stages.append(dict(cfg=cfg, c=c, params=params, Y1=Y1, Y2=Y2, dY1=dY1, dY2=dY2, ws=ws, out=out))
+        del X
+    torch.cuda.synchronize()
+
+    def run(schedule, only=None):
+        for si in reversed(range(len(stages))):
+            if only is not None and si != only:
+                continue
+            st = stages[si]
+            if schedule == "pareprop":
+                B.rev_stack_backward_pareprop(st["c"], st["params"], st["Y1"], st["Y2"], st["dY1"], st["dY2"], side,
+                                              workspace=st["ws"], out=st["out"])
+            else:
+                B.rev_stack_backward_reprop(st["c"], st["params"], st["Y1"], st["Y2"], st["dY1"], st["dY2"],
+                                            workspace=st["ws"], out=st["out"])
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main_s)
+            fn()
+            e1.record(main_s)
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall, np.array([a.elapsed_time(z) for a, z in ev])
+
+    wall_p, ms_p = timed(lambda: run("pareprop"), args.steps, args.warmup)
+    wall_r, ms_r = timed(lambda: run("reprop"), args.steps, args.warmup)
+    per_stage = []
+    for si, st in enumerate(stages):
+        _, a = timed(lambda: run("pareprop", si), max(5, args.steps // 3), 2)
+        _, b = timed(lambda: run("reprop", si), max(5, args.steps // 3), 2)
+        cfg = st["cfg"]
+        per_stage.append({"stage": si + 1, "blocks": cfg["n_blocks"], "d_model": cfg["d_model"], "windows": cfg["batch"],
+                          "tokens": cfg["seq_len"], "pareprop_ms": float(np.median(a)), "reprop_ms": float(np.median(b)),
+                          "algorithmic_tflop": algorithmic_flops(cfg) / 1e12})
+    images = hier["images"]
+    flops = sum(algorithmic_flops(st["cfg"]) for st in stages)
+    value = images * args.steps / wall_p
+    print(json.dumps({
+        "metric": f"reversible backward images/s (PaReprop schedule), {args.workload}-shaped stage stacks",
+        "value": value, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_p / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {len(stages)} stages of window-attention shaped reversible stacks, "
+                               f"{images} images of 224x224", "schedule": "pareprop (2 HIP streams)"},
+        "pareprop": {"images_per_s": value, "ms_median": float(np.median(ms_p)), "ms_std": float(ms_p.std())},
+        "reprop": {"images_per_s": images * args.steps / wall_r, "ms_median": float(np.median(ms_r)),
+                   "ms_std": float(ms_r.std())},
+        "pareprop_over_reprop": float(np.median(ms_r)) / float(np.median(ms_p)),
+        "algorithmic_tflop_per_step": flops / 1e12,
+        "mfma_fraction_whole_path": flops / (float(np.median(ms_p)) * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
+        "stages": per_stage}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="vit_b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["all", "reprop", "pareprop"], default="all",
                     help="restrict the run to one schedule (for profiler runs); the JSON line then lacks the other")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples the oracle is timed on (0 = auto)")
+    ap.add_argument("--sweep-batch", default="",
+                    help="comma-separated batch sizes: time both schedules and report workspace bytes at each "
+                         "(the paper's throughput-vs-batch and memory-vs-batch comparisons); replaces the default run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -65,7 +220,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload in synth.HIERARCHIES:
+        bench_hierarchy(args, synth.HIERARCHIES[args.workload], B, synth, torch, np)
+        return
     cfg = dict(synth.CONFIGS[args.workload])
+    if args.sweep_batch:
+        sweep_batch(args, cfg, B, synth, torch, np)
+        return
     c = B.make_cfg(**cfg)
     Bsz = cfg["batch"]
 
@@ -147,6 +308,30 @@ def main():
 
     calibration_copy()
 
+    def measured_peaks():
+        # what this machine reaches on the two textbook yardsticks, so that fractions can be read against
+        # achievable as well as nominal peaks: a streaming device copy and a long square bf16 GEMM
+        # from the vendor library (torch.matmul); neither is part of the path
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        a = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+        b = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+        res = {}
+        for name, fn, work in (("copy_GBs", lambda: dst.copy_(src), 2 * src.numel() * 4 / 1e9),
+                               ("library_gemm_bf16_8192_TFLOPs", lambda: torch.matmul(a, b.t()), 2 * 8192 ** 3 / 1e12)):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            res[name] = work / (e0.elapsed_time(e1) / 10 * 1e-3)
+        return res
+
+    peaks = measured_peaks()
+
     flops = algorithmic_flops(cfg)
     ms_step = wall_p / args.steps * 1e3
     value = Bsz * args.steps / wall_p
@@ -201,6 +386,8 @@ def main():
                                      "reprop": flops / (float(np.median(ms_r)) * 1e-3) / (peak * 1e12)},
         "kernel_families": families,
         "roofline": roofline,
+        "measured_peaks": peaks,
+        "memory": memory_model(B, c, cfg),
         "workspace_bytes": int(ws.numel()),
         "paper_context": "paper reports whole-training-step gains only (A100 80GB, precision unstated): ViT ~0%, "
                          "up to +20% on Swin; no backward-only number",

@@ -93,14 +93,30 @@ int64_t rev_stack_param_count(const rev_cfg* cfg);
  * Negative error code on bad arguments.  Host only. */
 int64_t rev_stack_param_offset(const rev_cfg* cfg, int32_t block, int32_t tensor, int64_t* count);
 
-/* Bytes of device workspace any of the three entry points below needs for cfg
- * (one size covers all; a multiple of 256).  Negative error code on bad cfg.
+/* Bytes of device workspace that is enough for every entry point below
+ * (a multiple of 256).  Negative error code on bad cfg.
  * Holds: two activation slots (the per-block intermediates a gradient step
  * consumes; the second slot is what lets block i-1 be recomputed while block i
  * is still being differentiated, Sec. 3.2/3.3), a ring of three residual-stream
  * levels, two cotangent levels, gradient temporaries, transposed weight copies
  * and the partial sums of the deterministic reductions.  Host only. */
 int64_t rev_stack_workspace_bytes(const rev_cfg* cfg);
+
+/* Bytes of the smaller workspace that rev_stack_forward and
+ * rev_stack_backward_reprop accept: with one stream nothing of block i-1 is
+ * produced while block i is still being consumed, so ONE activation slot, two
+ * residual-stream levels and single gradient temporaries suffice.  The
+ * difference to rev_stack_workspace_bytes is the extra memory the parallel
+ * schedule pays for its speed (Sec. 3.3; memory trends, Sec. 5.2).  Host only. */
+int64_t rev_stack_workspace_bytes_reprop(const rev_cfg* cfg);
+
+/* Bytes of one activation slot: the intermediates of ONE block that a gradient
+ * step consumes (normalised inputs, QKV, attention output and row statistics,
+ * MLP pre-activation and activation).  Backpropagation without recomputation
+ * would keep one such slot, plus both residual streams, per block; the
+ * reversible schedules keep one (Reprop) or two (PaReprop) in total.  For the
+ * memory-versus-batch comparison of Sec. 5.2.  Host only. */
+int64_t rev_stack_slot_bytes(const rev_cfg* cfg);
 
 /* Forward map of the whole stack (Eq. 1 applied N times); stores no
  * activations beyond Y1, Y2.  X1, X2 in; Y1, Y2 out (float32 [B,T,D]).

@@ -21,6 +21,7 @@ MODES = {"fp32": REV_MODE_FP32, "bf16": REV_MODE_BF16}
 
 EXPORTS = (
     "rev_stack_check_cfg", "rev_stack_param_count", "rev_stack_param_offset", "rev_stack_workspace_bytes",
+    "rev_stack_workspace_bytes_reprop", "rev_stack_slot_bytes",
     "rev_stack_forward", "rev_stack_backward_reprop", "rev_stack_backward_pareprop", "rev_stack_backward_chain",
     "rev_profile_begin", "rev_profile_end", "rev_profile_kinds", "rev_profile_name", "rev_profile_is_flops",
     "rev_profile_get", "rev_last_error",
@@ -55,8 +56,9 @@ def lib():
         L.rev_stack_param_count.restype = i64
         L.rev_stack_param_offset.argtypes = [cp, i32, i32, ctypes.POINTER(i64)]
         L.rev_stack_param_offset.restype = i64
-        L.rev_stack_workspace_bytes.argtypes = [cp]
-        L.rev_stack_workspace_bytes.restype = i64
+        for n in ("rev_stack_workspace_bytes", "rev_stack_workspace_bytes_reprop", "rev_stack_slot_bytes"):
+            getattr(L, n).argtypes = [cp]
+            getattr(L, n).restype = i64
         L.rev_stack_forward.argtypes = [cp, vp, vp, vp, vp, vp, vp, i64, vp]
         L.rev_stack_forward.restype = ctypes.c_int
         bw = [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64]
@@ -115,12 +117,21 @@ def rev_stack_workspace_bytes(cfg: RevCfg) -> int:
     return _check(lib().rev_stack_workspace_bytes(ctypes.byref(cfg)))
 
 
+def rev_stack_workspace_bytes_reprop(cfg: RevCfg) -> int:
+    return _check(lib().rev_stack_workspace_bytes_reprop(ctypes.byref(cfg)))
+
+
+def rev_stack_slot_bytes(cfg: RevCfg) -> int:
+    return _check(lib().rev_stack_slot_bytes(ctypes.byref(cfg)))
+
+
 def param_dtype(cfg: RevCfg):
     return torch.bfloat16 if cfg.mode == REV_MODE_BF16 else torch.float32
 
 
-def alloc_workspace(cfg: RevCfg, device="cuda") -> torch.Tensor:
-    return torch.empty(rev_stack_workspace_bytes(cfg), dtype=torch.uint8, device=device)
+def alloc_workspace(cfg: RevCfg, device="cuda", reprop_only: bool = False) -> torch.Tensor:
+    n = rev_stack_workspace_bytes_reprop(cfg) if reprop_only else rev_stack_workspace_bytes(cfg)
+    return torch.empty(n, dtype=torch.uint8, device=device)
 
 
 def _ptr(t):

@@ -108,9 +108,15 @@ struct Layout {
     int64_t part_ln[2], part_col[2], part_wg[4];   // one per deferred reduction of a block
     int64_t total;
     int64_t part_wg_elems[4];
+    int64_t slot_bytes;
+    int ring_levels;
 };
 
-static Layout make_layout(const rev_cfg& c) {
+// compact = the layout of the sequential schedule (and of the forward map): nothing of block i-1
+// is produced while block i is still being consumed, so one activation slot, two residual levels and
+// one copy of each per-block gradient temporary are enough.  The full layout doubles those, which is
+// the extra memory the parallel schedule pays (Sec. 3.3, Sec. 5.2).
+static Layout make_layout(const rev_cfg& c, bool compact) {
     Layout L = {};
     const int64_t M = (int64_t)c.batch * c.seq_len, D = c.d_model, Dm = c.d_mlp;
     const int64_t es = (c.mode == REV_MODE_BF16) ? 2 : 4;
@@ -128,11 +134,12 @@ static Layout make_layout(const rev_cfg& c) {
         L.s_lse = take((int64_t)c.batch * c.n_heads * c.seq_len * 4) - base;
         L.s_st1 = take(M * 2 * 4) - base;
         L.s_st2 = take(M * 2 * 4) - base;
-        int64_t slot_bytes = off - base;
+        L.slot_bytes = off - base;
         L.slot[0] = base;
-        L.slot[1] = take(slot_bytes);
+        L.slot[1] = compact ? base : take(L.slot_bytes);
     }
-    for (int r = 0; r < 3; ++r)
+    L.ring_levels = compact ? 2 : 3;
+    for (int r = 0; r < L.ring_levels; ++r)
         for (int s = 0; s < 2; ++s) L.ring[r][s] = take(M * D * 4);
     for (int r = 0; r < 2; ++r)
         for (int s = 0; s < 2; ++s) L.cot[r][s] = take(M * D * 4);
@@ -140,11 +147,11 @@ static Layout make_layout(const rev_cfg& c) {
         L.cot2b[0] = take(M * D * es);
         L.cot2b[1] = take(M * D * es);
         L.gy1b[0] = take(M * D * es);
-        L.gy1b[1] = take(M * D * es);
+        L.gy1b[1] = compact ? L.gy1b[0] : take(M * D * es);
     }
     for (int r = 0; r < 2; ++r) {
-        L.dh[r] = take(M * Dm * es);
-        L.dqkv[r] = take(M * 3 * D * es);
+        L.dh[r] = (compact && r) ? L.dh[0] : take(M * Dm * es);
+        L.dqkv[r] = (compact && r) ? L.dqkv[0] : take(M * 3 * D * es);
     }
     L.dn = take(M * D * es);
     L.dO = take(M * D * es);
@@ -226,8 +233,8 @@ struct Runner {
     float* dparams;
     int M, D, Dm, H, dh, B, Tn;
 
-    Runner(const rev_cfg& cfg, const void* p, float* dp, void* w)
-        : c(cfg), L(make_layout(cfg)), ws((char*)w), params((const T*)p), dparams(dp) {
+    Runner(const rev_cfg& cfg, const void* p, float* dp, void* w, bool compact)
+        : c(cfg), L(make_layout(cfg, compact)), ws((char*)w), params((const T*)p), dparams(dp) {
         M = c.batch * c.seq_len; D = c.d_model; Dm = c.d_mlp; H = c.n_heads; dh = D / H; B = c.batch; Tn = c.seq_len;
     }
     template <typename U> U* at(int64_t off) const { return reinterpret_cast<U*>(ws + off); }
@@ -376,7 +383,7 @@ struct Runner {
     float* res(int lvl, int st, float* x_out1, float* x_out2) const {
         if (lvl == 0 && st == 0 && x_out1) return x_out1;
         if (lvl == 0 && st == 1 && x_out2) return x_out2;
-        return at<float>(L.ring[lvl % 3][st]);
+        return at<float>(L.ring[lvl % L.ring_levels][st]);
     }
 
     // schedule: 0 = Reprop, 1 = PaReprop, 2 = R chain only, 3 = V chain only
@@ -477,21 +484,21 @@ struct Runner {
     int forward(const float* X1, const float* X2, float* Y1, float* Y2, hipStream_t s) {
         const int N = c.n_blocks;
         for (int i = 1; i <= N; ++i) {
-            const float* x1 = (i == 1) ? X1 : at<float>(L.ring[(i - 1) % 3][0]);
-            const float* x2 = (i == 1) ? X2 : at<float>(L.ring[(i - 1) % 3][1]);
-            float* y1 = (i == N) ? Y1 : at<float>(L.ring[i % 3][0]);
-            float* y2 = (i == N) ? Y2 : at<float>(L.ring[i % 3][1]);
+            const float* x1 = (i == 1) ? X1 : at<float>(L.ring[(i - 1) % L.ring_levels][0]);
+            const float* x2 = (i == 1) ? X2 : at<float>(L.ring[(i - 1) % L.ring_levels][1]);
+            float* y1 = (i == N) ? Y1 : at<float>(L.ring[i % L.ring_levels][0]);
+            float* y2 = (i == N) ? Y2 : at<float>(L.ring[i % L.ring_levels][1]);
             RC(forward_block(s, i - 1, x1, x2, y1, y2));
         }
         return REV_OK;
     }
 };
 
-static int check_common(const rev_cfg* cfg, const void* ws, int64_t ws_bytes) {
+static int check_common(const rev_cfg* cfg, const void* ws, int64_t ws_bytes, bool compact) {
     RC(check_cfg(cfg));
     if (!ws) { set_error("workspace is null"); return REV_EINVAL; }
     if (((uintptr_t)ws & 255) != 0) { set_error("workspace must be 256-byte aligned"); return REV_EINVAL; }
-    Layout L = make_layout(*cfg);
+    Layout L = make_layout(*cfg, compact);
     if (ws_bytes < L.total) {
         set_error("workspace too small: need " + std::to_string(L.total) + " bytes, got " + std::to_string(ws_bytes));
         return REV_EWORKSPACE;
@@ -504,7 +511,8 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 static int backward_entry(int schedule, const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
                           const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1o, float* X2o,
                           float* dparams, void* ws, int64_t ws_bytes, void* sv, void* sr) {
-    RC(check_common(cfg, ws, ws_bytes));
+    const bool compact = schedule == 0;          // the sequential schedule runs in the smaller layout
+    RC(check_common(cfg, ws, ws_bytes, compact));
     if (!params || !Y1 || !Y2 || !dY1 || !dY2 || !dX1 || !dX2 || !dparams) {
         set_error("a required pointer is null"); return REV_EINVAL;
     }
@@ -514,10 +522,10 @@ static int backward_entry(int schedule, const rev_cfg* cfg, const void* params, 
     }
     if (schedule == 1 && sv == sr) { set_error("PaReprop needs two different streams"); return REV_EINVAL; }
     if (cfg->mode == REV_MODE_BF16) {
-        Runner<bf16> r(*cfg, params, dparams, ws);
+        Runner<bf16> r(*cfg, params, dparams, ws, compact);
         return r.backward(schedule, Y1, Y2, dY1, dY2, dX1, dX2, X1o, X2o, (hipStream_t)sv, (hipStream_t)sr);
     }
-    Runner<float> r(*cfg, params, dparams, ws);
+    Runner<float> r(*cfg, params, dparams, ws, compact);
     return r.backward(schedule, Y1, Y2, dY1, dY2, dX1, dX2, X1o, X2o, (hipStream_t)sv, (hipStream_t)sr);
 }
 
@@ -548,21 +556,33 @@ int64_t rev_stack_param_offset(const rev_cfg* cfg, int32_t block, int32_t tensor
 int64_t rev_stack_workspace_bytes(const rev_cfg* cfg) {
     int rc = check_cfg(cfg);
     if (rc) return rc;
-    return make_layout(*cfg).total;
+    return make_layout(*cfg, false).total;
+}
+
+int64_t rev_stack_workspace_bytes_reprop(const rev_cfg* cfg) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    return make_layout(*cfg, true).total;
+}
+
+int64_t rev_stack_slot_bytes(const rev_cfg* cfg) {
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    return make_layout(*cfg, true).slot_bytes;
 }
 
 int rev_stack_forward(const rev_cfg* cfg, const void* params, const float* X1, const float* X2, float* Y1, float* Y2,
                       void* ws, int64_t ws_bytes, void* stream) {
-    RC(check_common(cfg, ws, ws_bytes));
+    RC(check_common(cfg, ws, ws_bytes, true));
     if (!params || !X1 || !X2 || !Y1 || !Y2) { set_error("a required pointer is null"); return REV_EINVAL; }
     if (!aligned16(params) || !aligned16(X1) || !aligned16(X2) || !aligned16(Y1) || !aligned16(Y2)) {
         set_error("every buffer must be 16-byte aligned"); return REV_EINVAL;
     }
     if (cfg->mode == REV_MODE_BF16) {
-        Runner<bf16> r(*cfg, params, nullptr, ws);
+        Runner<bf16> r(*cfg, params, nullptr, ws, true);
         return r.forward(X1, X2, Y1, Y2, (hipStream_t)stream);
     }
-    Runner<float> r(*cfg, params, nullptr, ws);
+    Runner<float> r(*cfg, params, nullptr, ws, true);
     return r.forward(X1, X2, Y1, Y2, (hipStream_t)stream);
 }
 

@@ -45,6 +45,28 @@ def test_param_count_and_offsets_match_the_layout(name):
     assert ws > 0 and ws % 256 == 0
 
 
+def _up(n):
+    return (n + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_workspace_sizes_of_the_two_schedules(name):
+    """One activation slot holds n2, h, a, n1, qkv, o (activation type), the softmax row
+    statistics and the two LayerNorm statistics (float32); the sequential schedule's workspace is
+    smaller than the parallel one's by one slot, one residual level and the second copies of the
+    per-block gradient temporaries (gY1 copy, dh, dqkv)."""
+    cfg = synth.CONFIGS[name]
+    c = B.make_cfg(**cfg)
+    D, Dm, T, Bsz, H = cfg["d_model"], cfg["d_mlp"], cfg["seq_len"], cfg["batch"], cfg["n_heads"]
+    M = Bsz * T
+    es = 2 if cfg["mode"] == "bf16" else 4
+    slot = (_up(M * D * es) * 3 + _up(M * Dm * es) * 2 + _up(M * 3 * D * es) + _up(Bsz * H * T * 4) + 2 * _up(M * 8))
+    assert B.rev_stack_slot_bytes(c) == slot
+    full, small = B.rev_stack_workspace_bytes(c), B.rev_stack_workspace_bytes_reprop(c)
+    extra = slot + 2 * _up(M * D * 4) + _up(M * Dm * es) + _up(M * 3 * D * es) + (_up(M * D * es) if es == 2 else 0)
+    assert full - small == extra and small % 256 == 0
+
+
 def test_bad_configs_are_rejected():
     good = dict(synth.CONFIGS["tiny"])
     assert B.rev_stack_check_cfg(B.make_cfg(**good)) == 0
@@ -66,7 +88,8 @@ def test_bad_configs_are_rejected():
 def test_null_pointers_and_short_workspace_fail_before_any_gpu_work():
     L = B.lib()
     c = B.make_cfg(**synth.CONFIGS["tiny"])
-    need = B.rev_stack_workspace_bytes(c)
+    need = B.rev_stack_workspace_bytes_reprop(c)
+    full = B.rev_stack_workspace_bytes(c)
     fake = ctypes.c_void_p(0x10000)          # never dereferenced: validation comes first
     vp = ctypes.c_void_p
     # null workspace
@@ -82,7 +105,12 @@ def test_null_pointers_and_short_workspace_fail_before_any_gpu_work():
     args[2] = vp(0x10004)                                             # misaligned Y1
     assert L.rev_stack_backward_reprop(*args, None) == -1
     args[2] = fake
+    args[12] = need - 1
+    assert L.rev_stack_backward_reprop(*args, None) == -2            # short for the sequential schedule
+    args[12] = need
     s = vp(0x1234)
+    assert L.rev_stack_backward_pareprop(*args, s, vp(0x5678)) == -2  # enough for Reprop only
+    args[12] = full
     assert L.rev_stack_backward_pareprop(*args, s, s) == -1           # same stream twice
     assert "different streams" in B.rev_last_error()
     assert L.rev_stack_backward_chain(*args, None, 5) == -1

@@ -110,7 +110,7 @@ def test_vit_b_full_batch_in_bench_configuration():
     assert lin <= 1e-3
 
 
-@pytest.mark.parametrize("name,batch", [("vit_s", 6), ("roberta_base", 2), ("vit_h", 2)])
+@pytest.mark.parametrize("name,batch", [("vit_s", 6), ("roberta_base", 2), ("vit_h", 2), ("roberta_large", 1)])
 def test_full_depth_full_width_reduced_batch(name, batch):
     """All blocks at full width (32 blocks and head_dim 80 for vit_h, T = 512 for
     roberta_base), batch reduced to what the oracle finishes in seconds."""
@@ -140,7 +140,7 @@ def test_full_batch_shapes_run_and_agree_between_schedules():
     """Every bf16 config at its full batch: finite outputs, exact reconstruction
     tolerance on the inputs (known without the oracle: Y comes from the GPU forward
     of X here, so only self-consistency is claimed), PaReprop == Reprop."""
-    for name in ("vit_s", "roberta_base", "vit_h"):
+    for name in ("vit_s", "roberta_base", "vit_h", "roberta_large_t1024"):
         cfg = dict(synth.CONFIGS[name])
         print(f"[case] {name} full batch", flush=True)
         flat = synth.make_params(cfg, seed=0)

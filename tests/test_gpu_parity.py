@@ -23,6 +23,11 @@ SHAPES = {
     "dh128_T1": dict(n_blocks=2, d_model=256, n_heads=2, d_mlp=264, seq_len=1, batch=5),
     "vit_s_slice": dict(n_blocks=3, d_model=384, n_heads=6, d_mlp=1536, seq_len=197, batch=3),
     "one_sample_T300": dict(n_blocks=1, d_model=64, n_heads=2, d_mlp=64, seq_len=300, batch=1),
+    # window-attention shaped stages (49 tokens, head_dim 32): narrow first stage, many-headed last stage
+    "window_stage1": dict(n_blocks=2, d_model=96, n_heads=3, d_mlp=384, seq_len=49, batch=7),
+    "window_stage4": dict(n_blocks=1, d_model=768, n_heads=24, d_mlp=3072, seq_len=49, batch=2),
+    # 1024 tokens: keys and values no longer fit the on-chip tile pair, the streamed attention path runs
+    "T1024_dh64": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=1024, batch=1),
 }
 
 
@@ -111,6 +116,39 @@ def test_short_workspace_is_an_error_on_the_gpu_too():
     cfg = dict(SHAPES["tiny"])
     c = gpu_cfg(cfg)
     flat, _, x, _, _ = make_case(cfg)
-    ws = torch.empty(B.rev_stack_workspace_bytes(c) - 256, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.rev_stack_workspace_bytes_reprop(c) - 256, dtype=torch.uint8, device="cuda")
     with pytest.raises(B.RevError, match="workspace too small"):
         B.rev_stack_forward(c, to_dev(flat), to_dev(x), to_dev(x), workspace=ws)
+
+
+@pytest.mark.parametrize("name,mode", [("tiny", "fp32"), ("ragged_dh64", "bf16"), ("vit_s_slice", "bf16")])
+def test_reprop_in_its_smaller_workspace_gives_the_same_bits(name, mode):
+    """The sequential schedule and the forward map run in the one-slot workspace
+    (guard bytes behind it stay untouched) and return exactly what they return in
+    the large one; the parallel schedule refuses the small one."""
+    cfg = dict(SHAPES[name], mode=mode)
+    print(f"[case] small workspace {name} mode={mode}", flush=True)
+    flat, blocks, x, dy1, dy2 = make_case(cfg, seed=5)
+    c = gpu_cfg(cfg)
+    params = to_dev(flat, B.param_dtype(c))
+    small = B.rev_stack_workspace_bytes_reprop(c)
+    assert small < B.rev_stack_workspace_bytes(c)
+    guard = 4096
+    buf = torch.empty(small + guard, dtype=torch.uint8, device="cuda")
+    buf.fill_(0xA5)
+    ws_small, ws_full = buf[:small], B.alloc_workspace(c)
+    X, dY1, dY2 = to_dev(x), to_dev(dy1), to_dev(dy2)
+    Y1, Y2 = B.rev_stack_forward(c, params, X, X, workspace=ws_full)
+    y1s, y2s = B.rev_stack_forward(c, params, X, X, workspace=ws_small)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, y1s) and torch.equal(Y2, y2s)
+    a = B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws_full, want_inputs=True)
+    b = B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws_small, want_inputs=True)
+    side = torch.cuda.Stream()
+    p = B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side, workspace=ws_full, want_inputs=True)
+    torch.cuda.synchronize()
+    for k in ("dX1", "dX2", "dparams", "X1", "X2"):
+        assert torch.equal(a[k], b[k]) and torch.equal(a[k], p[k]), k
+    assert bool((buf[small:] == 0xA5).all()), "wrote past the small workspace"
+    with pytest.raises(B.RevError, match="workspace too small"):
+        B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side, workspace=ws_small)
