@@ -393,6 +393,53 @@ def main():
                          "up to +20% on Swin; no backward-only number",
     }
 
+    # ---- whole training step (the quantity the paper's throughput figures are about): forward of
+    # the stack, reversible backward, AdamW update of every parameter; dY stays the fixed synthetic
+    # cotangent (no head / loss), the weights really change from step to step
+    master = params.float().clone()
+    mom1, mom2 = torch.zeros_like(master), torch.zeros_like(master)
+    Yt1, Yt2 = torch.empty_like(Y1), torch.empty_like(Y2)
+    tstep = [0]
+
+    def train_step(schedule):
+        def fn():
+            tstep[0] += 1
+            B.rev_stack_forward(c, params, X, X, workspace=ws, Y1=Yt1, Y2=Yt2)
+            if schedule == "pareprop":
+                B.rev_stack_backward_pareprop(c, params, Yt1, Yt2, dY1, dY2, side, workspace=ws, out=out)
+            else:
+                B.rev_stack_backward_reprop(c, params, Yt1, Yt2, dY1, dY2, workspace=ws, out=out)
+            B.rev_adamw_step(master, out["dparams"], mom1, mom2, tstep[0], lr=1e-5,
+                             params_bf16=params if cfg["mode"] == "bf16" else None)
+            if cfg["mode"] != "bf16":
+                params.copy_(master)
+        return fn
+
+    tsteps = max(5, args.steps // 2)
+    _, ms_tp = timed(train_step("pareprop"), tsteps, 3)
+    _, ms_tr = timed(train_step("reprop"), tsteps, 3)
+    _, ms_fwd = timed(lambda: B.rev_stack_forward(c, params, X, X, workspace=ws, Y1=Yt1, Y2=Yt2), tsteps, 2)
+
+    def adam_only():
+        tstep[0] += 1
+        B.rev_adamw_step(master, out["dparams"], mom1, mom2, tstep[0], lr=1e-5,
+                         params_bf16=params if cfg["mode"] == "bf16" else None)
+    _, ms_opt = timed(adam_only, tsteps, 2)
+    nparam = int(params.numel())
+    opt_bytes = nparam * (30 if cfg["mode"] == "bf16" else 28)
+    line["training_step"] = {
+        "what": "rev_stack_forward + reversible backward + rev_adamw_step, no head/loss, synthetic cotangents",
+        "pareprop": {"samples_per_s": Bsz / (float(np.median(ms_tp)) * 1e-3), "ms_median": float(np.median(ms_tp))},
+        "reprop": {"samples_per_s": Bsz / (float(np.median(ms_tr)) * 1e-3), "ms_median": float(np.median(ms_tr))},
+        "pareprop_over_reprop": float(np.median(ms_tr)) / float(np.median(ms_tp)),
+        "forward_ms": float(np.median(ms_fwd)),
+        "adamw_ms": float(np.median(ms_opt)),
+        "adamw_GBs": opt_bytes / (float(np.median(ms_opt)) * 1e-3) / 1e9,
+        "adamw_hbm_fraction": opt_bytes / (float(np.median(ms_opt)) * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "parameters": nparam,
+        "finite_after_steps": bool(torch.isfinite(master).all().item()),
+    }
+
     if not args.no_cpu_baseline:
         from oracle import rev_oracle as O
         blocks = O.unpack_params(flat, cfg["n_blocks"], cfg["d_model"], cfg["d_mlp"])

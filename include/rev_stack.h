@@ -157,6 +157,26 @@ int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params,
                                 void* workspace, int64_t workspace_bytes,
                                 void* stream_grad, void* stream_recompute);
 
+/* Optimizer update of a training step: AdamW, the optimizer of the paper's
+ * throughput experiments (Sec. 5, experimental setup; the paper gives neither
+ * formula nor hyper-parameters, so this is the published update with decoupled
+ * weight decay, eps outside the square root, step counter from 1):
+ *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   theta -= lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps)
+ *                   + weight_decay * theta ).
+ * All buffers are device memory of n elements, updated in place:
+ *   master      float32 weights (in float32 mode these ARE the stack's params);
+ *   params_bf16 nullable; if given, receives master rounded to bf16 (nearest
+ *               even): the copy the bf16-mode entry points read;
+ *   grad        float32 gradient, e.g. dparams of a backward call (not modified);
+ *   m, v        float32 moments (zero before step 1).
+ * float32 arithmetic throughout.  Enqueues on `stream` and returns.
+ * REV_EINVAL on null/misaligned pointers (16 bytes; 8 for params_bf16), n <= 0,
+ * step < 1, beta outside [0,1) or a negative lr/eps/weight_decay. */
+int rev_adamw_step(int64_t n, float* master, void* params_bf16, const float* grad,
+                   float* m, float* v, int32_t step, float lr, float beta1, float beta2,
+                   float eps, float weight_decay, void* stream);
+
 /* Measurement aid for the hidden-recompute fraction: runs only one of the two
  * chains of the backward pass on `stream`.  chain = 0: the recomputation chain
  * R_N..R_1 alone (writes X1_out/X2_out if given).  chain = 1: the gradient

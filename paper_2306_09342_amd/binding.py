@@ -23,6 +23,7 @@ EXPORTS = (
     "rev_stack_check_cfg", "rev_stack_param_count", "rev_stack_param_offset", "rev_stack_workspace_bytes",
     "rev_stack_workspace_bytes_reprop", "rev_stack_slot_bytes",
     "rev_stack_forward", "rev_stack_backward_reprop", "rev_stack_backward_pareprop", "rev_stack_backward_chain",
+    "rev_adamw_step",
     "rev_profile_begin", "rev_profile_end", "rev_profile_kinds", "rev_profile_name", "rev_profile_is_flops",
     "rev_profile_get", "rev_last_error",
 )
@@ -68,6 +69,9 @@ def lib():
         L.rev_stack_backward_pareprop.restype = ctypes.c_int
         L.rev_stack_backward_chain.argtypes = bw + [vp, i32]
         L.rev_stack_backward_chain.restype = ctypes.c_int
+        f32 = ctypes.c_float
+        L.rev_adamw_step.argtypes = [i64, vp, vp, vp, vp, vp, i32, f32, f32, f32, f32, f32, vp]
+        L.rev_adamw_step.restype = ctypes.c_int
         for n in ("rev_profile_begin", "rev_profile_end", "rev_profile_kinds"):
             getattr(L, n).argtypes = []
             getattr(L, n).restype = ctypes.c_int
@@ -207,6 +211,19 @@ def rev_stack_backward_chain(cfg, params, Y1, Y2, dY1, dY2, chain, workspace=Non
     args, res = _backward_args(cfg, params, Y1, Y2, dY1, dY2, workspace, want_inputs, out)
     _check(lib().rev_stack_backward_chain(*args, _stream_handle(stream), int(chain)))
     return res
+
+
+def rev_adamw_step(master, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01,
+                   params_bf16=None, stream=None):
+    """In-place AdamW update of the float32 `master` weights and moments `m`, `v` from the float32
+    gradient; `params_bf16` (optional) receives the bf16 copy of the new weights."""
+    for t in (master, grad, m, v):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == master.numel()
+    if params_bf16 is not None:
+        assert params_bf16.is_cuda and params_bf16.dtype == torch.bfloat16 and params_bf16.is_contiguous()
+        assert params_bf16.numel() == master.numel()
+    _check(lib().rev_adamw_step(master.numel(), _ptr(master), _ptr(params_bf16), _ptr(grad), _ptr(m), _ptr(v),
+                                int(step), lr, beta1, beta2, eps, weight_decay, _stream_handle(stream)))
 
 
 def rev_profile_begin():

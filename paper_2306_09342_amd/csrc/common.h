@@ -4,6 +4,7 @@
 #include <hip/hip_bf16.h>
 #include <stdint.h>
 #include <string>
+#include <cmath>
 
 #include "rev_stack.h"
 
@@ -32,6 +33,7 @@ enum Kind {
     K_COLSUM,        // bias gradients (column sums), first stage
     K_REDUCE,        // fixed-order second stage of column sums / split reductions
     K_CONVERT,       // dtype conversion and weight transposes
+    K_OPTIM,         // optimizer update
     K_COUNT
 };
 
@@ -42,6 +44,10 @@ struct ProfScope {
     Kind kind; hipStream_t stream; void* rec;
 };
 bool profiling();
+
+// AdamW update of n packed elements (optimizer.hip)
+int adamw_step(hipStream_t s, int64_t n, float* master, void* params_bf16, const float* grad, float* m, float* v,
+               int step, float lr, float beta1, float beta2, float eps, float weight_decay);
 
 // ---- small device helpers ------------------------------------------------------
 __device__ __forceinline__ float to_f(float v) { return v; }

@@ -30,8 +30,8 @@ static double g_prof_ms[K_COUNT];
 static int64_t g_prof_n[K_COUNT];
 static double g_prof_work[K_COUNT];
 static const char* g_kind_names[K_COUNT] = {"gemm_nt", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd",
-                                            "ln_bwd", "colsum", "reduce", "convert"};
-static const int g_kind_flops[K_COUNT] = {1, 1, 1, 1, 0, 0, 0, 0, 0};
+                                            "ln_bwd", "colsum", "reduce", "convert", "optimizer"};
+static const int g_kind_flops[K_COUNT] = {1, 1, 1, 1, 0, 0, 0, 0, 0, 0};
 
 bool profiling() { return g_prof_on; }
 
@@ -605,6 +605,21 @@ int rev_stack_backward_chain(const rev_cfg* cfg, const void* params, const float
     if (chain != 0 && chain != 1) { set_error("chain must be 0 or 1"); return REV_EINVAL; }
     return backward_entry(chain == 0 ? 2 : 3, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws,
                           ws_bytes, stream, stream);
+}
+
+int rev_adamw_step(int64_t n, float* master, void* params_bf16, const float* grad, float* m, float* v,
+                   int32_t step, float lr, float beta1, float beta2, float eps, float weight_decay, void* stream) {
+    if (n <= 0) { set_error("adamw: n must be positive"); return REV_EINVAL; }
+    if (!master || !grad || !m || !v) { set_error("adamw: a required pointer is null"); return REV_EINVAL; }
+    if (step < 1) { set_error("adamw: the step counter starts at 1"); return REV_EINVAL; }
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f) || !(lr >= 0.f) ||
+        !(weight_decay >= 0.f)) {
+        set_error("adamw: need 0 <= beta < 1, eps >= 0, lr >= 0, weight_decay >= 0"); return REV_EINVAL;
+    }
+    if (!aligned16(master) || !aligned16(grad) || !aligned16(m) || !aligned16(v) || ((uintptr_t)params_bf16 & 7) != 0) {
+        set_error("adamw: float32 buffers must be 16-byte aligned, the bf16 copy 8-byte aligned"); return REV_EINVAL;
+    }
+    return adamw_step((hipStream_t)stream, n, master, params_bf16, grad, m, v, step, lr, beta1, beta2, eps, weight_decay);
 }
 
 int rev_profile_begin(void) {

@@ -116,3 +116,15 @@ def test_null_pointers_and_short_workspace_fail_before_any_gpu_work():
     assert L.rev_stack_backward_chain(*args, None, 5) == -1
     assert L.rev_profile_kinds() >= 6
     assert L.rev_profile_name(0) == b"gemm_nt"
+
+
+def test_adamw_arguments_are_validated_before_any_gpu_work():
+    L = B.lib()
+    fake = ctypes.c_void_p(0x10000)
+    ok = [1024, fake, None, fake, fake, fake, 1, 1e-3, 0.9, 0.999, 1e-8, 0.01, None]
+    for idx, val in ((0, 0), (1, None), (3, None), (4, None), (5, None), (6, 0), (7, -1.0), (8, 1.0), (9, -0.1),
+                     (10, -1e-8), (11, -0.5), (1, ctypes.c_void_p(0x10004)), (2, ctypes.c_void_p(0x10002))):
+        args = list(ok)
+        args[idx] = val
+        assert L.rev_adamw_step(*args) == -1, (idx, val)
+        assert "adamw" in B.rev_last_error()
