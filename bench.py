@@ -172,7 +172,11 @@ def bench_hierarchy(args, hier, B, synth, torch, np):
         _, a = timed(lambda: run("pareprop", si), max(5, args.steps // 3), 2)
         _, b = timed(lambda: run("reprop", si), max(5, args.steps // 3), 2)
         cfg = st["cfg"]
-        per_stage.append({"stage": si + 1, "blocks": cfg["n_blocks"], "d_model": cfg["d_model"], "windows": cfg["batch"],
+        B.rev_profile_begin()
+        for _ in range(3):
+            run("reprop", si)
+        fam = {k: round(ms / 3, 4) for k, (ms, n, work, is_flops) in B.rev_profile_end().items() if n}
+        per_stage.append({"stage": si + 1, "family_ms": fam, "blocks": cfg["n_blocks"], "d_model": cfg["d_model"], "windows": cfg["batch"],
                           "tokens": cfg["seq_len"], "pareprop_ms": float(np.median(a)), "reprop_ms": float(np.median(b)),
                           "algorithmic_tflop": algorithmic_flops(cfg) / 1e12})
     images = hier["images"]

@@ -137,13 +137,19 @@ template int ln_forward<bf16, bf16>(hipStream_t, const float*, const bf16*, cons
 // of) are folded across the 4 wavefronts in LDS in wavefront order and written
 // as one partial row [dgamma | dbeta | colsum(out)] per block.
 constexpr int LNB_ROWS = 32;
+// Rows per block: LNB_ROWS, or more (a multiple of 4) once that would give above 2048 partial rows
+static int ln_bwd_rows_per_block(int M) {
+    int rpb = LNB_ROWS;
+    if ((M + rpb - 1) / rpb > 2048) rpb = (((M + 2047) / 2048) + 3) / 4 * 4;
+    return rpb;
+}
 
 template <typename TA, typename TP, int MAXJ>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, const float* __restrict__ x,
                                                      const float* __restrict__ stats, const TP* __restrict__ g,
                                                      const float* __restrict__ r, float* __restrict__ out,
                                                      TA* __restrict__ outb, float* __restrict__ partial,
-                                                     int M, int D) {
+                                                     int M, int D, int rows_per_block) {
     extern __shared__ float lds[];   // [3 * D]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int nch = D >> 2;
@@ -156,8 +162,8 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
         int c = lane + 64 * j;
         gg[j] = (c < nch) ? load4(g + 4 * c) : f4{0.f, 0.f, 0.f, 0.f};
     }
-    const int row0 = blockIdx.x * LNB_ROWS;
-    const int row1 = min(M, row0 + LNB_ROWS);
+    const int row0 = blockIdx.x * rows_per_block;
+    const int row1 = min(M, row0 + rows_per_block);
     for (int row = row0 + wave; row < row1; row += 4) {
         const float mean = stats[2 * (int64_t)row], rstd = stats[2 * (int64_t)row + 1];
         const int64_t base = (int64_t)row * D;
@@ -254,7 +260,20 @@ __global__ __launch_bounds__(256) void reduce_multi_kernel(RedArgs a) {
         const int64_t i = (int64_t)lb * 16 + cg;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         if (i < g.n4) {
-            for (int p = pl; p < g.P; p += 16) {
+            // 4 loads in flight per thread; the additions stay in ascending row order
+            int p = pl;
+            for (; p + 48 < g.P; p += 64) {
+                const float* q = g.partial + (int64_t)p * g.stride + 4 * i;
+                const float4 v0 = *reinterpret_cast<const float4*>(q);
+                const float4 v1 = *reinterpret_cast<const float4*>(q + 16 * g.stride);
+                const float4 v2 = *reinterpret_cast<const float4*>(q + 32 * g.stride);
+                const float4 v3 = *reinterpret_cast<const float4*>(q + 48 * g.stride);
+                acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+                acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+                acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+                acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
+            }
+            for (; p < g.P; p += 16) {
                 float4 v = *reinterpret_cast<const float4*>(g.partial + (int64_t)p * g.stride + 4 * i);
                 acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
             }
@@ -313,14 +332,16 @@ int reduce_rows2(hipStream_t s, const float* partial, int P, int64_t stride, int
 }
 
 int64_t ln_bwd_partial_elems(int M, int D) {
-    return (int64_t)((M + LNB_ROWS - 1) / LNB_ROWS) * 3 * D;
+    const int rpb = ln_bwd_rows_per_block(M);
+    return (int64_t)((M + rpb - 1) / rpb) * 3 * D;
 }
 
 template <typename TA, typename TP>
 int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats, const TP* g,
                 const float* r, float* out, TA* outb, float* dgb, float* dbias,
                 float* partial, int M, int D, RedSeg* defer) {
-    const int nblk = (M + LNB_ROWS - 1) / LNB_ROWS;
+    const int rpb = ln_bwd_rows_per_block(M);
+    const int nblk = (M + rpb - 1) / rpb;
     {
         ProfScope ps(K_LN_BWD, s, (double)M * D * (sizeof(TA) + 4 + 4 + 4 + (outb ? sizeof(TA) : 0)));
         dim3 grid(nblk), block(256);
@@ -333,7 +354,7 @@ int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats,
                 REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 64 * J * 16)); \
                 attr_set = true;                                                                                        \
             }                                                                                                           \
-            hipLaunchKernelGGL(kern, grid, block, shmem, s, dn, x, stats, g, r, out, outb, partial, M, D);          \
+            hipLaunchKernelGGL(kern, grid, block, shmem, s, dn, x, stats, g, r, out, outb, partial, M, D, rpb);     \
         } break;
             CASE(2) CASE(4) CASE(8) CASE(16) CASE(32)
 #undef CASE

@@ -205,14 +205,19 @@ constexpr int WG_BR = 64;             // tokens per step
 
 // The token reduction is cut into S ranges so that tiles * S fills, but does not exceed, the
 // workgroup slots of the chip (256 CUs x 2 resident workgroups): one full round, no ragged second one.
+// Narrow layers with very many tokens (window-attention stages: a handful of tiles, thousands of
+// steps) get up to 128 ranges; the partial sums stay below 64 MB.
 static int wgrad_splits(int M, int N, int K) {
     const int tiles = ((N + WG_BP - 1) / WG_BP) * ((K + WG_BQ - 1) / WG_BQ);
     int S = 512 / tiles;
     const int steps = (M + WG_BR - 1) / WG_BR;
-    if (S > steps) S = steps;
-    if (S > 16) S = 16;
+    if (S > steps / 4) S = steps / 4;                          // at least 4 steps per range
+    const int64_t cap = ((int64_t)64 << 20) / ((int64_t)N * K * 4);   // at most 64 MB of partial sums
+    if (S > cap) S = (int)cap;
+    if (S > 128) S = 128;
     if (S < 1) S = 1;
-    return S;
+    const int sps = (steps + S - 1) / S;
+    return (steps + sps - 1) / sps;                            // no empty ranges
 }
 int64_t wgrad_partial_elems(int M, int N, int K) {
     const int S = wgrad_splits(M, N, K);
