@@ -19,6 +19,7 @@
 // through LDS once and leaves in full contiguous rows with 16-byte accesses,
 // the epilogue (bias, GELU, GELU', residual) applied on the way out.
 #include "mfma.h"
+#include <type_traits>
 
 namespace rev {
 
@@ -91,6 +92,7 @@ __device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_
     }
     return acc;
 }
+
 
 template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* __restrict__ A, int64_t lda,
@@ -194,6 +196,110 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int a_row = (wm * TM * 32 + fr) * ROWB;
     const int b_row = A_BYTES + (wn * TN * 32 + fr) * ROWB;
 
+    // The default shape (128x128x64 tile, 64x64 per wavefront, 2 stages) takes the hand-placed path.
+    constexpr bool HANDPLACED = (TM == 2 && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
+    if constexpr (HANDPLACED) {
+        const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(unsigned char, smem);
+        unsigned a_addr[4], b_addr[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            a_addr[kk] = lds0 + a_row + koff[kk];
+            b_addr[kk] = lds0 + b_row + koff[kk];
+        }
+        // K-major B: base addresses of the two 32-column fragments of this wavefront (step 0, low half)
+        unsigned bt_addr[2] = {0, 0};
+        if (BKM) {
+            const int jj = lane & 15, q = lane >> 4;
+            const int r = (q >> 1) * 8 + (jj >> 2);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = wn * 64 + j * 32 + (q & 1) * 16 + 4 * (jj & 3);
+                const int pos = (c >> 3) ^ (4 * (r & 3));
+                bt_addr[j] = lds0 + A_BYTES + r * 256 + pos * 16 + (c & 7) * 2;
+            }
+        }
+        // has_next is a compile-time tag: a branch around the loads inside the loop body makes the
+        // register allocator shuttle all 64 accumulators between register files every iteration
+        auto stage_body = [&](auto stage_tag, auto next_tag, int kt) {
+            constexpr int SOFF = decltype(stage_tag)::value * STAGE;
+            constexpr bool has_next = decltype(next_tag)::value;
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+            __builtin_amdgcn_s_barrier();
+            u32x4_t a[4][2], b[4][2];
+            auto read_group = [&](auto kk_tag) {
+                constexpr int kk = decltype(kk_tag)::value;
+                a[kk][0] = lds_read_b128(a_addr[kk], SOFF);
+                a[kk][1] = lds_read_b128(a_addr[kk], SOFF + 32 * ROWB);
+                if (BKM) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        b[kk][j] = join64(lds_read_tr16_b64(bt_addr[j], SOFF + kk * 16 * 256),
+                                          lds_read_tr16_b64(bt_addr[j], SOFF + kk * 16 * 256 + 4 * 256));
+                } else {
+                    b[kk][0] = lds_read_b128(b_addr[kk], SOFF);
+                    b[kk][1] = lds_read_b128(b_addr[kk], SOFF + 32 * ROWB);
+                }
+            };
+            auto products = [&](int kk) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) acc[j][i] = mfma32(as_bf16x8(b[kk][j]), as_bf16x8(a[kk][i]), acc[j][i]);
+                __builtin_amdgcn_sched_barrier(0);       // the products stay between their wait and the next one
+            };
+            using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
+            using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
+            constexpr int RPK = BKM ? 6 : 4;              // LDS reads per step
+#if defined(REV_EXP_FLOOD)
+            if (!BKM) {
+                read_group(I0{}); read_group(I1{}); read_group(I2{}); read_group(I3{});
+                if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
+                lds_wait4<3 * RPK>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
+                lds_wait4<2 * RPK>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);
+                lds_wait4<1 * RPK>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
+                lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]);       products(3);
+            } else {
+                read_group(I0{}); read_group(I1{}); read_group(I2{});
+                if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
+                lds_wait4<2 * RPK>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
+                read_group(I3{});
+                lds_wait4<2 * RPK>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);
+                lds_wait4<1 * RPK>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
+                lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]);       products(3);
+            }
+#else
+            // one step ahead, as the compiler would order it, but every product group waits only for
+            // its own operands (the reads of the step after it stay in flight)
+#if defined(REV_EXP_DMAFIRST)
+            if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
+            read_group(I0{}); read_group(I1{});
+#else
+            read_group(I0{}); read_group(I1{});
+#if !defined(REV_EXP_NOLOAD)
+            if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
+#endif
+#endif
+            lds_wait4<RPK>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
+            read_group(I2{});
+            lds_wait4<RPK>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);
+            read_group(I3{});
+            lds_wait4<RPK>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
+            lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]);   products(3);
+#endif
+        };
+        using S0 = std::integral_constant<int, 0>; using S1 = std::integral_constant<int, 1>;
+        int kt = 0;
+        for (; kt + 2 < nk; kt += 2) {
+            stage_body(S0{}, std::true_type{}, kt);
+            stage_body(S1{}, std::true_type{}, kt + 1);
+        }
+        if (kt + 2 == nk) {
+            stage_body(S0{}, std::true_type{}, kt);
+            stage_body(S1{}, std::false_type{}, kt + 1);
+        } else {
+            stage_body(S0{}, std::false_type{}, kt);
+        }
+    } else
     for (int kt = 0; kt < nk; ++kt) {
         if (NS == 1) {
             // single buffer: latency is hidden by the other workgroups resident on the CU
@@ -351,6 +457,8 @@ static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
     switch (g_nt_variant) {
         case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
 #ifdef REV_TUNE_VARIANTS
+        case 34: return launch_dma<128, 128, 2, 2, 32, 4, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
+        case 35: return launch_dma<128, 128, 2, 2, 32, 3, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
         case 20: return launch_dma<128, 128, 2, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
         case 25: return launch_dma<256, 128, 4, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
         case 27: return launch_dma<256, 256, 2, 2, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);

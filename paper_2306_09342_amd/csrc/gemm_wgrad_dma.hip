@@ -13,6 +13,7 @@
 //
 // Tokens beyond M and columns beyond N / K are fetched from a block of zeros.
 #include "mfma.h"
+#include <type_traits>
 
 namespace rev {
 
@@ -82,6 +83,70 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
     for (int s = 0; s < NS - 1; ++s)
         if (s < nsteps) issue(s, s);
 
+    if constexpr (NS == 2) {
+        // Hand-placed fragment reads (see mfma.h): one step ahead, every product group waits only
+        // for its own 8 transpose reads.  Stage parity and "is there a next stage" are compile-time
+        // tags so that the loop body has no branch.
+        const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(unsigned char, smem);
+        unsigned g_addr[2], a_addr[2];
+        {
+            const int jj = lane & 15, q = lane >> 4;
+            const int r = (q >> 1) * 8 + (jj >> 2);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int cg = wp * 64 + i * 32 + (q & 1) * 16 + 4 * (jj & 3);
+                const int ca = wq * 64 + i * 32 + (q & 1) * 16 + 4 * (jj & 3);
+                g_addr[i] = lds0 + r * 256 + (((cg >> 3) ^ (4 * (r & 3))) * 16) + (cg & 7) * 2;
+                a_addr[i] = lds0 + WD_TILE + r * 256 + (((ca >> 3) ^ (4 * (r & 3))) * 16) + (ca & 7) * 2;
+            }
+        }
+        auto body = [&](auto stage_tag, auto next_tag, int st) {
+            constexpr int SOFF = decltype(stage_tag)::value * WD_STAGE;
+            constexpr bool has_next = decltype(next_tag)::value;
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+            __builtin_amdgcn_s_barrier();
+            u32x4_t a[4][2], b[4][2];
+            auto read_group = [&](auto kk_tag) {
+                constexpr int kk = decltype(kk_tag)::value;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    a[kk][i] = join64(lds_read_tr16_b64(g_addr[i], SOFF + kk * 16 * 256),
+                                      lds_read_tr16_b64(g_addr[i], SOFF + kk * 16 * 256 + 4 * 256));
+                    b[kk][i] = join64(lds_read_tr16_b64(a_addr[i], SOFF + kk * 16 * 256),
+                                      lds_read_tr16_b64(a_addr[i], SOFF + kk * 16 * 256 + 4 * 256));
+                }
+            };
+            auto products = [&](int kk) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(as_bf16x8(a[kk][i]), as_bf16x8(b[kk][j]), acc[i][j]);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
+            using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
+            read_group(I0{}); read_group(I1{});
+            if (has_next) issue(st + 1, 1 - decltype(stage_tag)::value);
+            lds_wait4<8>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
+            read_group(I2{});
+            lds_wait4<8>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);
+            read_group(I3{});
+            lds_wait4<8>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
+            lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]); products(3);
+        };
+        using S0 = std::integral_constant<int, 0>; using S1 = std::integral_constant<int, 1>;
+        int st = 0;
+        for (; st + 2 < nsteps; st += 2) {
+            body(S0{}, std::true_type{}, st);
+            body(S1{}, std::true_type{}, st + 1);
+        }
+        if (st + 2 == nsteps) {
+            body(S0{}, std::true_type{}, st);
+            body(S1{}, std::false_type{}, st + 1);
+        } else if (st + 1 == nsteps) {
+            body(S0{}, std::false_type{}, st);
+        }
+    } else
     for (int st = 0; st < nsteps; ++st) {
         if (st + NS - 2 < nsteps) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * LPW));
         else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));

@@ -62,6 +62,30 @@ __device__ __forceinline__ bf16x8_t tr_frag_swz(const unsigned char* tile, int r
     return u.v;
 }
 
+// ---- hand-placed LDS fragment reads -------------------------------------------------------------
+// The compiler waits for ALL outstanding LDS reads (lgkmcnt(0)) before the first product that uses
+// any of them, which serialises the read latency with the matrix-core work twice per stage.  The
+// reads below are therefore issued as inline assembly, all of a stage's groups up front (or two
+// groups ahead), and every product group waits only for its own operands: LDS reads return in
+// order, so "at most n still outstanding" means the oldest ones have landed.  The wait statements
+// carry the fragment registers as read-write operands, which pins the products behind them.
+__device__ __forceinline__ u32x4_t lds_read_b128(unsigned addr, int imm) {
+    u32x4_t r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(imm) : "memory");
+    return r;
+}
+__device__ __forceinline__ u32x2_t lds_read_tr16_b64(unsigned addr, int imm) {
+    u32x2_t r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(imm) : "memory");
+    return r;
+}
+template <int N>
+__device__ __forceinline__ void lds_wait4(u32x4_t& a0, u32x4_t& a1, u32x4_t& b0, u32x4_t& b1) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1) : "n"(N));
+}
+__device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
+__device__ __forceinline__ u32x4_t join64(u32x2_t lo, u32x2_t hi) { return u32x4_t{lo[0], lo[1], hi[0], hi[1]}; }
+
 // 64 bytes of zeros (never written): the source of direct-to-LDS loads that fall outside a matrix
 static __device__ u32x4_t g_zero_chunk[4];
 
