@@ -133,8 +133,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     // chunk c of row r is kept at position c ^ swz(r): 16 consecutive rows x one chunk -> 16 distinct bank groups
     auto swz = [](int r) { return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
 
-    // per-lane source pointers of this wavefront's loads (advance BK elements per stage)
-    const bf16* src[LPW];
+    // Sources of this wavefront's loads: a scalar base per operand (the tile's first row / column,
+    // advanced along K per stage) plus a 32-bit per-lane byte offset inside the tile's panel, which
+    // is what the scalar-base addressing form of the load takes: no 64-bit vector adds per load.
+    // Rows beyond M or N re-read the last valid row; K-major B columns beyond N re-read the last
+    // valid 8 columns (such output rows / columns are never stored).
+    unsigned voff[LPW];
     int dst[LPW];
 #pragma unroll
     for (int t = 0; t < LPW; ++t) {
@@ -144,29 +148,31 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         const int row = ii * RPI + lane / CPR;
         const int chunk = (lane % CPR) ^ swz(row);
         if (isA) {
-            src[t] = A + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8;
+            voff[t] = (unsigned)(min(row, M - 1 - m0) * lda * 2 + chunk * 16);
             dst[t] = ii * 1024;
         } else if (!BKM) {
-            src[t] = B + (int64_t)min(n0 + row, N - 1) * ldb + chunk * 8;
+            voff[t] = (unsigned)(min(row, N - 1 - n0) * ldb * 2 + chunk * 16);
             dst[t] = A_BYTES + ii * 1024;
         } else {
             // 4 contraction rows of 16 chunks per load; chunk c of row r at position c ^ (4 * (r & 3))
             const int krow = ii * 4 + (lane >> 4);
-            const int col = n0 + (((lane & 15) ^ (4 * (krow & 3))) * 8);
-            src[t] = (col < N) ? B + (int64_t)krow * ldb + col : nullptr;    // null: columns beyond N read zeros
+            const int col = min(((lane & 15) ^ (4 * (krow & 3))) * 8, N - 8 - n0);
+            voff[t] = (unsigned)(krow * ldb * 2 + col * 2);
             dst[t] = A_BYTES + ii * 1024;
         }
     }
-    const int64_t bstep = BKM ? (int64_t)BK * ldb : (int64_t)BK;       // B advance per stage
-    const bf16* zero = reinterpret_cast<const bf16*>(g_zero_chunk);
+    const char* a_base = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+    const char* b_base = reinterpret_cast<const char*>(BKM ? B + n0 : B + (int64_t)n0 * ldb);
+    const int64_t bstep = BKM ? (int64_t)BK * ldb * 2 : (int64_t)BK * 2;       // B advance per stage, bytes
     // loads t0 <= t < t1 of the stage (the whole stage: 0, LPW)
     auto issue_part = [&](int kt, int stage, int t0, int t1) {
+        const char* ak = a_base + (int64_t)kt * (BK * 2);
+        const char* bk = b_base + kt * bstep;
 #pragma unroll
         for (int t = 0; t < LPW; ++t) {
             if (t < t0 || t >= t1) continue;
             const bool isA = (NW * t) < IA;
-            const bf16* p = isA ? src[t] + (int64_t)kt * BK
-                                : ((!BKM || src[t]) ? src[t] + kt * bstep : zero);   // only K-major B can fall outside
+            const char* p = (isA ? ak : bk) + voff[t];
             __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(void, smem + stage * STAGE + dst[t]), 16, 0, 0);
         }
     };
@@ -220,6 +226,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         }
         // has_next is a compile-time tag: a branch around the loads inside the loop body makes the
         // register allocator shuttle all 64 accumulators between register files every iteration
+        // this path issues its global loads in the scalar-base form
+        auto issue = [&](int kt, int stage) {
+            const char* ak = a_base + (int64_t)kt * (BK * 2);
+            const char* bk = b_base + kt * bstep;
+            const unsigned sbase = lds0 + stage * STAGE;
+#pragma unroll
+            for (int t = 0; t < LPW; ++t)
+                dma16_sbase((NW * t) < IA ? ak : bk, voff[t], sbase + dst[t]);
+        };
         auto stage_body = [&](auto stage_tag, auto next_tag, int kt) {
             constexpr int SOFF = decltype(stage_tag)::value * STAGE;
             constexpr bool has_next = decltype(next_tag)::value;

@@ -100,6 +100,34 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
                 a_addr[i] = lds0 + WD_TILE + r * 256 + (((ca >> 3) ^ (4 * (r & 3))) * 16) + (ca & 7) * 2;
             }
         }
+        // Full steps (all 64 token rows inside M) are loaded in the scalar-base form: per-lane 32-bit
+        // offsets fixed for the whole kernel, the scalar base advancing by 64 rows per step; tile
+        // columns beyond N / K re-read the last valid 8 (those outputs are never stored).  Only a
+        // ragged last step needs the zero-filling form above.
+        unsigned voff_g[4], voff_a[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            voff_g[t] = (unsigned)(rowl[t] * ldg * 2 + min(chunk[t] * 8, N - 8 - p0) * 2);
+            voff_a[t] = (unsigned)(rowl[t] * lda * 2 + min(chunk[t] * 8, K - 8 - q0) * 2);
+        }
+        const char* g_base = reinterpret_cast<const char*>(G + p0);
+        const char* a_base = reinterpret_cast<const char*>(A + q0);
+        auto issue_fast = [&](int st, int stage) {
+            const int64_t mbase = (int64_t)(step0 + st) * WD_BR;
+            const char* gs = g_base + mbase * ldg * 2;
+            const char* as = a_base + mbase * lda * 2;
+            const unsigned sb = lds0 + stage * WD_STAGE;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int i = wave + 4 * t;
+                dma16_sbase(gs, voff_g[t], sb + i * 1024);
+                dma16_sbase(as, voff_a[t], sb + WD_TILE + i * 1024);
+            }
+        };
+        auto issue_any = [&](int st, int stage) {
+            if ((step0 + st + 1) * WD_BR <= M) issue_fast(st, stage);
+            else issue(st, stage);
+        };
         auto body = [&](auto stage_tag, auto next_tag, int st) {
             constexpr int SOFF = decltype(stage_tag)::value * WD_STAGE;
             constexpr bool has_next = decltype(next_tag)::value;
@@ -126,7 +154,7 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
             using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
             using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
             read_group(I0{}); read_group(I1{});
-            if (has_next) issue(st + 1, 1 - decltype(stage_tag)::value);
+            if (has_next) issue_any(st + 1, 1 - decltype(stage_tag)::value);
             lds_wait4<8>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
             read_group(I2{});
             lds_wait4<8>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);

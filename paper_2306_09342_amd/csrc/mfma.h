@@ -86,6 +86,14 @@ __device__ __forceinline__ void lds_wait4(u32x4_t& a0, u32x4_t& a1, u32x4_t& b0,
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
 __device__ __forceinline__ u32x4_t join64(u32x2_t lo, u32x2_t hi) { return u32x4_t{lo[0], lo[1], hi[0], hi[1]}; }
 
+// Direct-to-LDS load of 16 bytes per lane in the scalar-base form: global address = sbase + voff
+// (per-lane 32-bit byte offset), LDS destination = lds_addr (wavefront-uniform) + 16 * lane.
+// Written out because the compiler otherwise rebuilds 64-bit per-lane pointers inside loops.
+__device__ __forceinline__ void dma16_sbase(const void* sbase, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
+}
+
 // 64 bytes of zeros (never written): the source of direct-to-LDS loads that fall outside a matrix
 static __device__ u32x4_t g_zero_chunk[4];
 
