@@ -59,10 +59,24 @@ __device__ __forceinline__ void st_bf16x4(void* p, f32x4_t v) {
     *reinterpret_cast<bf16x4_t*>(p) = b;
 }
 
-// 4 consecutive output columns n..n+3 of row m
+// The epilogue operand of 4 consecutive output columns n..n+3 of row m (residual stream or saved
+// pre-activation), loaded ahead of the arithmetic so that all loads of a panel are in flight together.
+template <int KIND>
+__device__ __forceinline__ f32x4_t epi_load4(const Epi& e, int m, int n) {
+    const int64_t idx = (int64_t)m * e.ldo + n;
+    if (KIND == EPI_RESIDUAL) return *reinterpret_cast<const f32x4_t*>(e.res + idx);
+    if (KIND == EPI_GELU_BWD) {
+        // the 4 bf16 values stay packed (2 registers) until epi_store4 unpacks them
+        const u32x2_t u = *reinterpret_cast<const u32x2_t*>(reinterpret_cast<const bf16*>(e.aux) + idx);
+        return f32x4_t{__uint_as_float(u[0]), __uint_as_float(u[1]), 0.f, 0.f};
+    }
+    return f32x4_t{0.f, 0.f, 0.f, 0.f};
+}
+
+// 4 consecutive output columns n..n+3 of row m; `opnd` is what epi_load4 returned for them
 // (returns the float32 values behind the stored output, for the fused column sums)
 template <int KIND>
-__device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_t acc, f32x4_t bv) {
+__device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_t acc, f32x4_t bv, f32x4_t opnd) {
     const int64_t idx = (int64_t)m * e.ldo + n;
     if (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) acc += bv;
     if (KIND == EPI_BIAS) {
@@ -74,15 +88,14 @@ __device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_
         for (int k = 0; k < 4; ++k) a[k] = acc[k] * gelu_cdf(acc[k]);
         st_bf16x4(reinterpret_cast<bf16*>(e.out2) + idx, a);
     } else if (KIND == EPI_RESIDUAL) {
-        const f32x4_t r = *reinterpret_cast<const f32x4_t*>(e.res + idx);
-        *reinterpret_cast<f32x4_t*>(e.outf + idx) = r + e.sign * acc;
+        *reinterpret_cast<f32x4_t*>(e.outf + idx) = opnd + e.sign * acc;
     } else if (KIND == EPI_GELU_BWD) {
-        const f32x4_t h = ld_bf16x4(reinterpret_cast<const bf16*>(e.aux) + idx);
+        const unsigned u0 = __float_as_uint(opnd[0]), u1 = __float_as_uint(opnd[1]);
+        const f32x4_t h = {__uint_as_float(u0 << 16), __uint_as_float(u0 & 0xFFFF0000u),
+                           __uint_as_float(u1 << 16), __uint_as_float(u1 & 0xFFFF0000u)};
         f32x4_t o;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            o[k] = acc[k] * (gelu_cdf(h[k]) + h[k] * gelu_pdf(h[k]));
-        }
+        for (int k = 0; k < 4; ++k) o[k] = acc[k] * (gelu_cdf(h[k]) + h[k] * gelu_pdf(h[k]));
         st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, o);
         return o;
     } else if (KIND == EPI_PLAIN) {
@@ -92,7 +105,6 @@ __device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_
     }
     return acc;
 }
-
 
 template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* __restrict__ A, int64_t lda,
@@ -180,6 +192,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     // With one wavefront per SIMD the loads of the next stage are handed out in slices between the
     // product groups of the current one, so the matrix cores start right after the barrier.
     constexpr bool SPREAD = (NW == 4 && TM * TN >= 16 && NS == 2 && LPW % (BK / 16) == 0);
+    constexpr bool HANDPLACED_SHAPE = (TM == 2 && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
+
+    // Epilogue geometry (a wavefront's 32-row panels leave through LDS in full rows) and, for the
+    // epilogues that read a second operand (residual stream, saved pre-activation), that operand:
+    // it does not depend on the products, so it is requested before the main loop and has landed
+    // long before it is needed.
+    constexpr int CW = TN * 32, CP = CW + 4;
+    constexpr int LPR = CW / 4;                           // lanes per row
+    constexpr int RPP = 64 / LPR;                         // rows per pass
+    constexpr int NP = 32 / RPP;
+    const int c4 = lane % LPR, rr = lane / LPR;
+    const int n = n0 + wn * CW + 4 * c4;
+    // (float32 residual rows cost 4 registers each: only the first panel's are held across the main
+    // loop, the second panel's are requested when the epilogue starts)
+    constexpr int PRE = !HANDPLACED_SHAPE ? 0 : (KIND == EPI_GELU_BWD ? TM : (KIND == EPI_RESIDUAL ? 1 : 0));
+    f32x4_t opnd_pre[TM][NP];
+    if (PRE > 0 && n < N) {
+#pragma unroll
+        for (int i = 0; i < PRE; ++i)
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                opnd_pre[i][p] = epi_load4<KIND>(epi, min(m0 + wm * TM * 32 + i * 32 + rr + p * RPP, M - 1), n);
+    }
 
     f32x16_t acc[TN][TM];
 #pragma unroll
@@ -203,7 +238,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int b_row = A_BYTES + (wn * TN * 32 + fr) * ROWB;
 
     // The default shape (128x128x64 tile, 64x64 per wavefront, 2 stages) takes the hand-placed path.
-    constexpr bool HANDPLACED = (TM == 2 && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
+    constexpr bool HANDPLACED = HANDPLACED_SHAPE;
     if constexpr (HANDPLACED) {
         const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(unsigned char, smem);
         unsigned a_addr[4], b_addr[4];
@@ -383,14 +418,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     }
 #endif
     // ---- epilogue through LDS, 32 rows at a time: wavefront-private [32][TN*32 + 4] float32 ----
-    constexpr int CW = TN * 32, CP = CW + 4;
-    constexpr int LPR = CW / 4;                           // lanes per row
-    constexpr int RPP = 64 / LPR;                         // rows per pass
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
     __builtin_amdgcn_s_barrier();                         // every wavefront is done with the operand stages
     float* ct = reinterpret_cast<float*>(smem) + wave * (32 * CP);
-    const int c4 = lane % LPR, rr = lane / LPR;
-    const int n = n0 + wn * CW + 4 * c4;
+    if ((KIND == EPI_RESIDUAL || KIND == EPI_GELU_BWD) && n < N) {
+#pragma unroll
+        for (int i = PRE; i < TM; ++i)
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                opnd_pre[i][p] = epi_load4<KIND>(epi, min(m0 + wm * TM * 32 + i * 32 + rr + p * RPP, M - 1), n);
+    }
     f32x4_t csum = {0.f, 0.f, 0.f, 0.f};
     f32x4_t bv = {0.f, 0.f, 0.f, 0.f};                    // this lane's 4 columns never change: one bias load
     if ((KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) && n < N)
@@ -405,14 +442,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
                 *reinterpret_cast<f32x4_t*>(ct + fr * CP + j * 32 + 8 * vq + 4 * g) = v;
             }
         // the region is private to the wavefront and LDS operations of a wavefront complete in order
+        // first every LDS read and every epilogue operand load of the 32-row panel, then the
+        // arithmetic and the stores: one memory round trip per panel instead of one per row group
+        f32x4_t v[NP], opnd[NP];
+        const int mrow = m0 + wm * TM * 32 + i * 32 + rr;
 #pragma unroll
-        for (int p = 0; p < 32 / RPP; ++p) {
-            const int row = p * RPP + rr;
-            const int m = m0 + wm * TM * 32 + i * 32 + row;
-            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(ct + row * CP + 4 * c4);
-            if (m < M && n < N) {
-                const f32x4_t o = epi_store4<KIND>(epi, m, n, v, bv);
-                if (KIND == EPI_GELU_BWD) csum += o;
+        for (int p = 0; p < NP; ++p) v[p] = *reinterpret_cast<const f32x4_t*>(ct + (p * RPP + rr) * CP + 4 * c4);
+        if (n < N) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) opnd[p] = opnd_pre[i][p];
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int m = mrow + p * RPP;
+                if (m < M) {
+                    const f32x4_t o = epi_store4<KIND>(epi, m, n, v[p], bv, opnd[p]);
+                    if (KIND == EPI_GELU_BWD) csum += o;
+                }
             }
         }
     }
