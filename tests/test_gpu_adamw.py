@@ -58,3 +58,55 @@ def test_adamw_rejects_bad_arguments():
         B.rev_adamw_step(t, t.clone(), t.clone(), t.clone(), 0, 1e-3)          # step counter starts at 1
     with pytest.raises(B.RevError):
         B.rev_adamw_step(t, t.clone(), t.clone(), t.clone(), 1, 1e-3, beta1=1.0)
+
+
+@pytest.mark.parametrize("mode", ["fp32", "bf16"])
+def test_three_training_steps_match_the_oracle_pipeline(mode):
+    """Forward, reversible backward (PaReprop) and AdamW chained for three steps, each side feeding
+    on its own previous step: the GPU path against oracle forward -> oracle reversible backward ->
+    oracle AdamW.  In bf16 mode the oracle's stack reads the bf16-rounded copy of its float64 master
+    weights, as the GPU's does of its float32 ones; the comparison is on the master weights."""
+    from oracle import rev_oracle as O
+    from paper_2306_09342_amd import synth
+    from parity_util import TOL, make_case, to_dev, gpu_cfg
+
+    cfg = dict(n_blocks=2, d_model=64, n_heads=2, d_mlp=128, seq_len=24, batch=3, mode=mode)
+    print(f"[case] three training steps mode={mode} cfg={cfg}", flush=True)
+    flat, _, x, dy1, dy2 = make_case(cfg, seed=11)
+    # eps = 1e-4: the key bias has an exactly zero gradient (softmax is shift invariant), which both
+    # sides reach only up to their own rounding noise (1e-9 in float32, 1e-17 in float64); AdamW divides by
+    # |g| + eps, so with eps at that noise level it would turn the noise into a step of its own
+    hp = dict(lr=1e-2, beta1=0.9, beta2=0.99, eps=1e-4, weight_decay=0.1)
+    hp64 = {k: float(np.float32(v)) for k, v in hp.items()}
+    c = gpu_cfg(cfg)
+    master = to_dev(flat)                                           # float32 master weights
+    params = master.clone() if mode == "fp32" else master.to(torch.bfloat16)
+    m = torch.zeros_like(master)
+    v = torch.zeros_like(master)
+    ws = B.alloc_workspace(c)
+    side = torch.cuda.Stream()
+    X, dY1, dY2 = to_dev(x), to_dev(dy1), to_dev(dy2)
+
+    r_master = flat.astype(np.float64)
+    r_m, r_v = np.zeros_like(r_master), np.zeros_like(r_master)
+    N, D, Dm, H = cfg["n_blocks"], cfg["d_model"], cfg["d_mlp"], cfg["n_heads"]
+    for step in range(1, 4):
+        Y1, Y2 = B.rev_stack_forward(c, params, X, X, workspace=ws)
+        g = B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side, workspace=ws)
+        B.rev_adamw_step(master, g["dparams"], m, v, step, params_bf16=params if mode == "bf16" else None, **hp)
+        if mode == "fp32":
+            params.copy_(master)
+        torch.cuda.synchronize()
+
+        r_params = r_master if mode == "fp32" else synth.to_bf16_grid(r_master.astype(np.float32)).astype(np.float64)
+        blocks = O.unpack_params(r_params, N, D, Dm)
+        y1, y2 = O.stack_forward(x.astype(np.float64), x.astype(np.float64), blocks, H, 1e-6)
+        _, _, grads, _, _ = O.stack_backward_reversible(y1, y2, blocks, H, dy1.astype(np.float64), dy2.astype(np.float64))
+        r_g = O.pack_params(grads)
+        r_master, r_m, r_v = A.adamw_step(r_master, r_g, r_m, r_v, step, lr=hp64["lr"], beta1=hp64["beta1"],
+                                          beta2=hp64["beta2"], eps=hp64["eps"], weight_decay=hp64["weight_decay"])
+        e = rel_err(master.cpu().numpy(), r_master)
+        print(f"[ok] step {step}: master weights {e:.2e}", flush=True)
+        # AdamW normalises the gradient, so a relative gradient error eps moves a weight by about lr * eps
+        # of a full step; the bound is the backward tolerance of the mode
+        assert e <= TOL[mode], (step, e)
