@@ -1,7 +1,7 @@
 // bf16 matrix-core GEMM entry points and the register-staged NT kernel.
 //
 //  gemm_nt_bf16 / gemm_nn_bf16   C = A * B^T  /  C = A * B  with fused epilogue.  Problems with
-//            K % 64 == 0 go to the pipelined direct-to-LDS kernel (gemm_nt_dma.hip); other K % 8 == 0
+//            K % 32 == 0 go to the pipelined direct-to-LDS kernel (gemm_nt_dma.hip); other K % 8 == 0
 //            problems to the register-staged kernel below (global -> VGPR -> LDS, padded tiles);
 //            anything else to the plain-ALU kernels.
 //  gemm_wgrad_bf16               dW[N,K] = G[M,N]^T * A[M,K]: picks the number of token ranges and
@@ -169,7 +169,7 @@ int gemm_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int6
 bool gemm_bf16_fast_path(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int N, int K, const Epi& epi) {
     const uintptr_t ptrs = (uintptr_t)A | (uintptr_t)B | (uintptr_t)epi.out | (uintptr_t)epi.out2 | (uintptr_t)epi.outf |
                            (uintptr_t)epi.bias | (uintptr_t)epi.res | (uintptr_t)epi.aux;
-    return K % 64 == 0 && N % 8 == 0 && (lda & 7) == 0 && (ldb & 7) == 0 && epi.ldo % 4 == 0 && (ptrs & 15) == 0;
+    return K % 32 == 0 && N % 8 == 0 && (lda & 7) == 0 && (ldb & 7) == 0 && epi.ldo % 4 == 0 && (ptrs & 15) == 0;
 }
 
 // C[M,N] = A[M,K] * B[K,N]   (B row-major [K, ldb]): the input-gradient form, weights as stored

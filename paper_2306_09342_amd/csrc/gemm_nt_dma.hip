@@ -1,4 +1,5 @@
-// NT GEMM, pipelined flavour:  C[M,N] (+epilogue) = A[M,K] * B[N,K]^T  for K % 64 == 0.
+// NT GEMM, pipelined flavour:  C[M,N] (+epilogue) = A[M,K] * B[N,K]^T  for K % 32 == 0 (64-wide stages
+// when K % 64 == 0, the tuned case).
 //
 // Operand tiles travel HBM -> LDS with the direct-to-LDS loads of gfx950
 // (global_load_lds_dwordx4): no staging registers, no LDS store instructions.
@@ -529,11 +530,14 @@ static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
         case 23: return launch_dma<256, 256, 2, 4, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
         case 24: return launch_dma<256, 256, 2, 4, 32, 4, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
 #endif
-        default: return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+        default:
+            // K a multiple of 32 but not of 64 (e.g. width 96): the same tile with 32-wide stages
+            if (K % 64 != 0) return launch_dma<128, 128, 2, 2, 32, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+            return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
     }
 }
 
-// Pipelined path; the caller has checked K % 64 == 0, N % 8 == 0 and 16-byte alignment of every row.
+// Pipelined path; the caller has checked K % 32 == 0, N % 8 == 0 and 16-byte alignment of every row.
 // b_kmajor = false: B is [N, K];  true: B is [K, N] (C = A * B).
 int gemm_bf16_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
                   int M, int N, int K, const Epi& epi, bool b_kmajor) {
