@@ -105,11 +105,15 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float* __restrict__ x
     }
 }
 
+// Register chunks (of 4 floats) each lane holds of a row: the smallest instantiated count that covers
+// D / 4 / 64.  Intermediate sizes matter: the kernels keep several row-long arrays in registers, so a
+// width of 768 (3 chunks) or 1280 (5) should not pay for 4 or 8.
 static int pick_maxj(int D) {
-    int nch = D / 4, need = (nch + 63) / 64;
-    int j = 2;
-    while (j < need) j *= 2;
-    return j;   // 2,4,8,16,32  (D <= 8192)
+    const int nch = D / 4, need = (nch + 63) / 64;
+    static const int sizes[] = {2, 3, 4, 5, 6, 8, 12, 16, 24, 32};
+    for (int j : sizes)
+        if (j >= need) return j;
+    return 64;   // D > 8192: no instantiation
 }
 
 template <typename TA, typename TP>
@@ -119,7 +123,7 @@ int ln_forward(hipStream_t s, const float* x, const TP* g, const TP* b, float ep
     dim3 grid(((M + 1) / 2 + 3) / 4), block(256);
     switch (pick_maxj(D)) {
 #define CASE(J) case J: hipLaunchKernelGGL((ln_fwd_kernel<TA, TP, J>), grid, block, 0, s, x, g, b, eps, y, stats, M, D); break;
-        CASE(2) CASE(4) CASE(8) CASE(16) CASE(32)
+        CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(8) CASE(12) CASE(16) CASE(24) CASE(32)
 #undef CASE
         default: set_error("ln_forward: d_model too large"); return REV_EINVAL;
     }
@@ -137,12 +141,21 @@ template int ln_forward<bf16, bf16>(hipStream_t, const float*, const bf16*, cons
 // of) are folded across the 4 wavefronts in LDS in wavefront order and written
 // as one partial row [dgamma | dbeta | colsum(out)] per block.
 constexpr int LNB_ROWS = 32;
-// Rows per block: LNB_ROWS, or more (a multiple of 4) once that would give above 2048 partial rows
+// Rows per block (a multiple of 4): LNB_ROWS for 32 k rows and more; fewer, down to 8, for shorter
+// inputs so that about 1024 blocks (4 per CU) are in flight; more once LNB_ROWS would give above 2048
+// partial rows.
 static int ln_bwd_rows_per_block(int M) {
     int rpb = LNB_ROWS;
     if ((M + rpb - 1) / rpb > 2048) rpb = (((M + 2047) / 2048) + 3) / 4 * 4;
+    else if (M < 1024 * LNB_ROWS) rpb = ((M + 1023) / 1024 + 3) / 4 * 4;
+    if (rpb < 8) rpb = 8;
     return rpb;
 }
+
+// Rows of 1024 floats and more (4+ register chunks per lane): the three column accumulators of a
+// wavefront live in its own slice of LDS instead of registers (lane-private slots, no synchronisation),
+// which roughly halves the register count and doubles the wavefronts in flight.
+template <int MAXJ> struct LnBwdCfg { static constexpr bool ACC_LDS = (MAXJ >= 4 && MAXJ <= 8); };
 
 template <typename TA, typename TP, int MAXJ>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, const float* __restrict__ x,
@@ -150,17 +163,29 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
                                                      const float* __restrict__ r, float* __restrict__ out,
                                                      TA* __restrict__ outb, float* __restrict__ partial,
                                                      int M, int D, int rows_per_block) {
-    extern __shared__ float lds[];   // [3 * D]
+    constexpr bool ACC_LDS = LnBwdCfg<MAXJ>::ACC_LDS;
+    extern __shared__ float lds[];   // [3 * D], or [4][3 * D] with ACC_LDS
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int nch = D >> 2;
-    f4 ag[MAXJ], ab[MAXJ], ao[MAXJ], gg[MAXJ];
+    constexpr int NACC = ACC_LDS ? 1 : MAXJ;
+    f4 ag[NACC], ab[NACC], ao[NACC], gg[MAXJ];
+    float* wacc = lds + (ACC_LDS ? wave * 3 * D : 0);            // [dgamma | dbeta | colsum(out)] of this wavefront
 #pragma unroll
     for (int j = 0; j < MAXJ; ++j) {
-        ag[j] = {0.f, 0.f, 0.f, 0.f};
-        ab[j] = {0.f, 0.f, 0.f, 0.f};
-        ao[j] = {0.f, 0.f, 0.f, 0.f};
         int c = lane + 64 * j;
         gg[j] = (c < nch) ? load4(g + 4 * c) : f4{0.f, 0.f, 0.f, 0.f};
+        if (ACC_LDS) {
+            if (c < nch) {
+                const f4 z = {0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<f4*>(wacc + 4 * c) = z;
+                *reinterpret_cast<f4*>(wacc + D + 4 * c) = z;
+                *reinterpret_cast<f4*>(wacc + 2 * D + 4 * c) = z;
+            }
+        } else {
+            ag[j % NACC] = {0.f, 0.f, 0.f, 0.f};
+            ab[j % NACC] = {0.f, 0.f, 0.f, 0.f};
+            ao[j % NACC] = {0.f, 0.f, 0.f, 0.f};
+        }
     }
     const int row0 = blockIdx.x * rows_per_block;
     const int row1 = min(M, row0 + rows_per_block);
@@ -181,9 +206,17 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
             if (c < nch) {
                 f4 xv = load4(x + base + 4 * c), d = load4(dn + base + 4 * c);
                 xh[j] = {(xv.x - mean) * rstd, (xv.y - mean) * rstd, (xv.z - mean) * rstd, (xv.w - mean) * rstd};
-                ab[j].x += d.x; ab[j].y += d.y; ab[j].z += d.z; ab[j].w += d.w;
-                ag[j].x += d.x * xh[j].x; ag[j].y += d.y * xh[j].y;
-                ag[j].z += d.z * xh[j].z; ag[j].w += d.w * xh[j].w;
+                if (ACC_LDS) {
+                    f4 b0 = *reinterpret_cast<f4*>(wacc + D + 4 * c), g0 = *reinterpret_cast<f4*>(wacc + 4 * c);
+                    b0.x += d.x; b0.y += d.y; b0.z += d.z; b0.w += d.w;
+                    g0.x += d.x * xh[j].x; g0.y += d.y * xh[j].y; g0.z += d.z * xh[j].z; g0.w += d.w * xh[j].w;
+                    *reinterpret_cast<f4*>(wacc + D + 4 * c) = b0;
+                    *reinterpret_cast<f4*>(wacc + 4 * c) = g0;
+                } else {
+                    ab[j % NACC].x += d.x; ab[j % NACC].y += d.y; ab[j % NACC].z += d.z; ab[j % NACC].w += d.w;
+                    ag[j % NACC].x += d.x * xh[j].x; ag[j % NACC].y += d.y * xh[j].y;
+                    ag[j % NACC].z += d.z * xh[j].z; ag[j % NACC].w += d.w * xh[j].w;
+                }
                 dh[j] = {d.x * gg[j].x, d.y * gg[j].y, d.z * gg[j].z, d.w * gg[j].w};
                 c1 += (dh[j].x + dh[j].y) + (dh[j].z + dh[j].w);
                 c2 += (dh[j].x * xh[j].x + dh[j].y * xh[j].y) + (dh[j].z * xh[j].z + dh[j].w * xh[j].w);
@@ -200,11 +233,25 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
                 o.y = rv[j].y + rstd * (dh[j].y - c1 - xh[j].y * c2);
                 o.z = rv[j].z + rstd * (dh[j].z - c1 - xh[j].z * c2);
                 o.w = rv[j].w + rstd * (dh[j].w - c1 - xh[j].w * c2);
-                ao[j].x += o.x; ao[j].y += o.y; ao[j].z += o.z; ao[j].w += o.w;
+                if (ACC_LDS) {
+                    f4 o0 = *reinterpret_cast<f4*>(wacc + 2 * D + 4 * c);
+                    o0.x += o.x; o0.y += o.y; o0.z += o.z; o0.w += o.w;
+                    *reinterpret_cast<f4*>(wacc + 2 * D + 4 * c) = o0;
+                } else {
+                    ao[j % NACC].x += o.x; ao[j % NACC].y += o.y; ao[j % NACC].z += o.z; ao[j % NACC].w += o.w;
+                }
                 store4(out + base + 4 * c, o);
                 if (outb) store4(outb + base + 4 * c, o);
             }
         }
+    }
+    float* prow = partial + (int64_t)blockIdx.x * 3 * D;
+    if (ACC_LDS) {
+        // fold the 4 wavefronts' slices in wavefront order
+        __syncthreads();
+        for (int i = threadIdx.x; i < 3 * D; i += 256)
+            prow[i] = ((lds[i] + lds[3 * D + i]) + lds[6 * D + i]) + lds[9 * D + i];
+        return;
     }
     // fold the 4 wavefronts' column accumulators in wavefront order
     for (int w = 0; w < 4; ++w) {
@@ -217,20 +264,19 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TA* __restrict__ dn, 
                     float* pb = lds + D + 4 * c;
                     float* po = lds + 2 * D + 4 * c;
                     if (w == 0) {
-                        pg[0] = ag[j].x; pg[1] = ag[j].y; pg[2] = ag[j].z; pg[3] = ag[j].w;
-                        pb[0] = ab[j].x; pb[1] = ab[j].y; pb[2] = ab[j].z; pb[3] = ab[j].w;
-                        po[0] = ao[j].x; po[1] = ao[j].y; po[2] = ao[j].z; po[3] = ao[j].w;
+                        pg[0] = ag[j % NACC].x; pg[1] = ag[j % NACC].y; pg[2] = ag[j % NACC].z; pg[3] = ag[j % NACC].w;
+                        pb[0] = ab[j % NACC].x; pb[1] = ab[j % NACC].y; pb[2] = ab[j % NACC].z; pb[3] = ab[j % NACC].w;
+                        po[0] = ao[j % NACC].x; po[1] = ao[j % NACC].y; po[2] = ao[j % NACC].z; po[3] = ao[j % NACC].w;
                     } else {
-                        pg[0] += ag[j].x; pg[1] += ag[j].y; pg[2] += ag[j].z; pg[3] += ag[j].w;
-                        pb[0] += ab[j].x; pb[1] += ab[j].y; pb[2] += ab[j].z; pb[3] += ab[j].w;
-                        po[0] += ao[j].x; po[1] += ao[j].y; po[2] += ao[j].z; po[3] += ao[j].w;
+                        pg[0] += ag[j % NACC].x; pg[1] += ag[j % NACC].y; pg[2] += ag[j % NACC].z; pg[3] += ag[j % NACC].w;
+                        pb[0] += ab[j % NACC].x; pb[1] += ab[j % NACC].y; pb[2] += ab[j % NACC].z; pb[3] += ab[j % NACC].w;
+                        po[0] += ao[j % NACC].x; po[1] += ao[j % NACC].y; po[2] += ao[j % NACC].z; po[3] += ao[j % NACC].w;
                     }
                 }
             }
         }
         __syncthreads();
     }
-    float* prow = partial + (int64_t)blockIdx.x * 3 * D;
     for (int i = threadIdx.x; i < 3 * D; i += 256) prow[i] = lds[i];
 }
 
@@ -345,18 +391,19 @@ int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats,
     {
         ProfScope ps(K_LN_BWD, s, (double)M * D * (sizeof(TA) + 4 + 4 + 4 + (outb ? sizeof(TA) : 0)));
         dim3 grid(nblk), block(256);
-        size_t shmem = (size_t)3 * D * sizeof(float);
         switch (pick_maxj(D)) {
 #define CASE(J) case J: {                                                                                            \
             auto kern = ln_bwd_kernel<TA, TP, J>;                                                                       \
+            constexpr int copies = LnBwdCfg<J>::ACC_LDS ? 4 : 1;                                                        \
+            const size_t shmem = (size_t)copies * 3 * D * sizeof(float);                                                \
             static bool attr_set = false;                                                                               \
             if (!attr_set) {                                                                                            \
-                REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 64 * J * 16)); \
+                REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, copies * 3 * 64 * J * 16)); \
                 attr_set = true;                                                                                        \
             }                                                                                                           \
             hipLaunchKernelGGL(kern, grid, block, shmem, s, dn, x, stats, g, r, out, outb, partial, M, D, rpb);     \
         } break;
-            CASE(2) CASE(4) CASE(8) CASE(16) CASE(32)
+            CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(8) CASE(12) CASE(16) CASE(24) CASE(32)
 #undef CASE
             default: set_error("ln_backward: d_model too large"); return REV_EINVAL;
         }
