@@ -431,19 +431,20 @@ static void row_split(int T, int* nblk, int* nw) {
 }
 
 // Rows of the streamed operands kept in LDS at a time: every (32-padded) row of the head when two such
-// tiles plus the row statistics fit in 80 KB -- then a workgroup loads once and never synchronises
-// again -- otherwise 64-row tiles.
+// tiles plus the row statistics fit in 128 KB -- then a workgroup loads once and never synchronises
+// again (measured faster than streaming even where only one such workgroup fits a CU: 257 tokens at
+// head_dim 80) -- otherwise 64-row tiles.
 template <int DHP>
 static int tile_rows(int T) {
     const int all = (T + 31) / 32 * 32;
     const size_t bytes = (size_t)2 * all * AtCfg<DHP>::PITCH * sizeof(uint16_t) + 2 * all * sizeof(float);
-    return bytes <= 80 * 1024 ? all : AT_ROWS;
+    return bytes <= 128 * 1024 ? all : AT_ROWS;
 }
 
 template <typename K>
 static int raise_lds(K kern, size_t shmem) {
     if (shmem > 64 * 1024)
-        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024));
+        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     return REV_OK;
 }
 
