@@ -22,6 +22,11 @@
 #include "mfma.h"
 #include <type_traits>
 
+// Compile-time switches for timing experiments only (never defined in the library build): REV_EXP_NOLOAD
+// leaves out the global loads of the main loop, REV_EXP_NOCOMPUTE its products (generic path), REV_EXP_NOEPI
+// the epilogue, so that the cost of each part can be read off a stand-alone run; REV_TUNE_VARIANTS adds the
+// tile shapes that were measured against the default one and rejected.
+
 namespace rev {
 
 // Normal CDF for the bf16 GELU epilogues: Phi(x) = 1/2 + x * P(x^2) on |x| <= 3.8, clamped outside, with a
@@ -301,34 +306,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
             using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
             constexpr int RPK = BKM ? 6 : 4;              // LDS reads per step
-#if defined(REV_EXP_FLOOD)
-            if (!BKM) {
-                read_group(I0{}); read_group(I1{}); read_group(I2{}); read_group(I3{});
-                if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
-                lds_wait4<3 * RPK>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
-                lds_wait4<2 * RPK>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);
-                lds_wait4<1 * RPK>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
-                lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]);       products(3);
-            } else {
-                read_group(I0{}); read_group(I1{}); read_group(I2{});
-                if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
-                lds_wait4<2 * RPK>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
-                read_group(I3{});
-                lds_wait4<2 * RPK>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);
-                lds_wait4<1 * RPK>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
-                lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]);       products(3);
-            }
-#else
             // one step ahead, as the compiler would order it, but every product group waits only for
             // its own operands (the reads of the step after it stay in flight)
-#if defined(REV_EXP_DMAFIRST)
-            if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
-            read_group(I0{}); read_group(I1{});
-#else
             read_group(I0{}); read_group(I1{});
 #if !defined(REV_EXP_NOLOAD)
             if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
-#endif
 #endif
             lds_wait4<RPK>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
             read_group(I2{});
@@ -336,7 +318,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             read_group(I3{});
             lds_wait4<RPK>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
             lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]);   products(3);
-#endif
         };
         using S0 = std::integral_constant<int, 0>; using S1 = std::integral_constant<int, 1>;
         int kt = 0;
