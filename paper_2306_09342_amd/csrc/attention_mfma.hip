@@ -57,6 +57,41 @@ __device__ __forceinline__ void load_tile(uint16_t* tile, const bf16* __restrict
     }
 }
 
+// The same load in two halves, for the streamed mode (64-row tiles): the global loads of the NEXT
+// tile are issued into registers before the products of the current one and stored to LDS after them,
+// so their latency is covered by the matrix-core work instead of being waited for at every tile.
+// A thread holds DHP / 32 16-byte pieces of one tile (enough for 64 rows with 4 or more wavefronts);
+// the launcher picks the plain-load instantiation for smaller workgroups.
+template <int DHP> struct TilePre {
+    static constexpr int N = DHP / 32;
+    u32x4_t v[N];
+};
+
+template <int DHP>
+__device__ __forceinline__ void tile_fetch(TilePre<DHP>& t, const bf16* __restrict__ base, int64_t ld, int row0,
+                                           int nrows, int dh) {
+    constexpr int CH = AtCfg<DHP>::CH;
+#pragma unroll
+    for (int i = 0; i < TilePre<DHP>::N; ++i) {
+        const int idx = threadIdx.x + i * blockDim.x;
+        const int row = idx / CH, ch = idx % CH;
+        const int gr = row0 + row;
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (idx < AT_ROWS * CH && gr < nrows && ch * 8 < dh) v = *reinterpret_cast<const u32x4_t*>(base + (int64_t)gr * ld + ch * 8);
+        t.v[i] = v;
+    }
+}
+template <int DHP>
+__device__ __forceinline__ void tile_store(uint16_t* tile, const TilePre<DHP>& t) {
+    constexpr int CH = AtCfg<DHP>::CH, PITCH = AtCfg<DHP>::PITCH;
+#pragma unroll
+    for (int i = 0; i < TilePre<DHP>::N; ++i) {
+        const int idx = threadIdx.x + i * blockDim.x;
+        const int row = idx / CH, ch = idx % CH;
+        if (idx < AT_ROWS * CH) *reinterpret_cast<u32x4_t*>(tile + row * PITCH + ch * 8) = t.v[i];
+    }
+}
+
 __device__ __forceinline__ bf16x8_t pack8(const float* p) {
     bf16x8_t r;
 #pragma unroll
@@ -74,7 +109,7 @@ __device__ __forceinline__ void store4_bf16(bf16* p, float a, float b, float c, 
 // ----------------------------------------------------------------------------------------
 // forward
 // ----------------------------------------------------------------------------------------
-template <int DHP>
+template <int DHP, bool PIPE>
 __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
                                                      float* __restrict__ lse, int T, int H, int dh, int trows) {
     // trows: streamed rows held in LDS at a time -- 64, or all ceil32(T) rows when they fit (one load, no
@@ -103,11 +138,27 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
         for (int v = 0; v < 16; ++v) accO[dt][v] = 0.f;
     float m = -INFINITY, l = 0.f;
 
+    // streamed mode (PIPE; trows == 64): the next 64-row tile is prefetched into registers during the products
+    constexpr bool pipe = PIPE;
+    TilePre<DHP> pk, pv;
+    if constexpr (pipe) {
+        tile_fetch<DHP>(pk, base + D, ld, 0, T, dh);
+        tile_fetch<DHP>(pv, base + 2 * D, ld, 0, T, dh);
+    }
     for (int t0 = 0; t0 < T; t0 += trows) {
       __syncthreads();
-      load_tile<DHP>(Ks0, base + D, ld, t0, T, dh, trows);
-      load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
+      if constexpr (pipe) {
+          tile_store<DHP>(Ks0, pk);
+          tile_store<DHP>(Vs0, pv);
+      } else {
+          load_tile<DHP>(Ks0, base + D, ld, t0, T, dh, trows);
+          load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
+      }
       __syncthreads();
+      if (pipe) if (t0 + trows < T) {
+          tile_fetch<DHP>(pk, base + D, ld, t0 + trows, T, dh);
+          tile_fetch<DHP>(pv, base + 2 * D, ld, t0 + trows, T, dh);
+      }
       for (int k0 = t0; k0 < min(T, t0 + trows); k0 += AT_ROWS) {
         const uint16_t* Ks = Ks0 + (k0 - t0) * C::PITCH;
         const uint16_t* Vs = Vs0 + (k0 - t0) * C::PITCH;
@@ -196,7 +247,7 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
 // ----------------------------------------------------------------------------------------
 // backward pass 1: dQ and delta (wavefront owns 32 query rows)
 // ----------------------------------------------------------------------------------------
-template <int DHP>
+template <int DHP, bool PIPE>
 __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                         const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                         bf16* __restrict__ dqkv, float* __restrict__ delta,
@@ -241,11 +292,26 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
 #pragma unroll
         for (int v = 0; v < 16; ++v) accQ[dt][v] = 0.f;
 
+    constexpr bool pipe = PIPE;
+    TilePre<DHP> pk, pv;
+    if constexpr (pipe) {
+        tile_fetch<DHP>(pk, base + D, ld, 0, T, dh);
+        tile_fetch<DHP>(pv, base + 2 * D, ld, 0, T, dh);
+    }
     for (int t0 = 0; t0 < T; t0 += trows) {
       __syncthreads();
-      load_tile<DHP>(Ks0, base + D, ld, t0, T, dh, trows);
-      load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
+      if constexpr (pipe) {
+          tile_store<DHP>(Ks0, pk);
+          tile_store<DHP>(Vs0, pv);
+      } else {
+          load_tile<DHP>(Ks0, base + D, ld, t0, T, dh, trows);
+          load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
+      }
       __syncthreads();
+      if (pipe) if (t0 + trows < T) {
+          tile_fetch<DHP>(pk, base + D, ld, t0 + trows, T, dh);
+          tile_fetch<DHP>(pv, base + 2 * D, ld, t0 + trows, T, dh);
+      }
       for (int k0 = t0; k0 < min(T, t0 + trows); k0 += AT_ROWS) {
         const uint16_t* Ks = Ks0 + (k0 - t0) * C::PITCH;
         const uint16_t* Vs = Vs0 + (k0 - t0) * C::PITCH;
@@ -306,7 +372,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
 // ----------------------------------------------------------------------------------------
 // backward pass 2: dK and dV (wavefront owns 32 key rows)
 // ----------------------------------------------------------------------------------------
-template <int DHP>
+template <int DHP, bool PIPE>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16* __restrict__ dqkv, int T, int H, int dh, int trows) {
@@ -337,17 +403,43 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
 #pragma unroll
         for (int v = 0; v < 16; ++v) { accK[dt][v] = 0.f; accV[dt][v] = 0.f; }
 
+    constexpr bool pipe = PIPE;
+    TilePre<DHP> pq, po;
+    float pre_l = 0.f, pre_d = 0.f;                                  // row statistics of the prefetched tile (thread r < 64: row r)
+    auto stats_fetch = [&](int row0) {
+        const int i = row0 + (int)threadIdx.x;
+        if ((int)threadIdx.x < AT_ROWS) {
+            pre_l = (i < T) ? lse[(int64_t)bh * T + i] * 1.4426950408889634f : INFINITY;
+            pre_d = (i < T) ? delta[(int64_t)bh * T + i] : 0.f;
+        }
+    };
+    if constexpr (pipe) {
+        tile_fetch<DHP>(pq, base, ld, 0, T, dh);
+        tile_fetch<DHP>(po, dob, D, 0, T, dh);
+        stats_fetch(0);
+    }
     for (int t0 = 0; t0 < T; t0 += trows) {
       __syncthreads();
-      load_tile<DHP>(Qs0, base, ld, t0, T, dh, trows);
-      load_tile<DHP>(Os0, dob, D, t0, T, dh, trows);
-      for (int r = threadIdx.x; r < trows; r += blockDim.x) {
-          const int i = t0 + r;
-          // log-sum-exp in the base-2 domain; +inf masks rows beyond the sequence (exp2(. - inf) = 0)
-          lse_s0[r] = (i < T) ? lse[(int64_t)bh * T + i] * 1.4426950408889634f : INFINITY;
-          del_s0[r] = (i < T) ? delta[(int64_t)bh * T + i] : 0.f;
+      if constexpr (pipe) {
+          tile_store<DHP>(Qs0, pq);
+          tile_store<DHP>(Os0, po);
+          if ((int)threadIdx.x < AT_ROWS) { lse_s0[threadIdx.x] = pre_l; del_s0[threadIdx.x] = pre_d; }
+      } else {
+          load_tile<DHP>(Qs0, base, ld, t0, T, dh, trows);
+          load_tile<DHP>(Os0, dob, D, t0, T, dh, trows);
+          for (int r = threadIdx.x; r < trows; r += blockDim.x) {
+              const int i = t0 + r;
+              // log-sum-exp in the base-2 domain; +inf masks rows beyond the sequence (exp2(. - inf) = 0)
+              lse_s0[r] = (i < T) ? lse[(int64_t)bh * T + i] * 1.4426950408889634f : INFINITY;
+              del_s0[r] = (i < T) ? delta[(int64_t)bh * T + i] : 0.f;
+          }
       }
       __syncthreads();
+      if (pipe) if (t0 + trows < T) {
+          tile_fetch<DHP>(pq, base, ld, t0 + trows, T, dh);
+          tile_fetch<DHP>(po, dob, D, t0 + trows, T, dh);
+          stats_fetch(t0 + trows);
+      }
       for (int i0 = t0; i0 < min(T, t0 + trows); i0 += AT_ROWS) {
         const uint16_t* Qs = Qs0 + (i0 - t0) * C::PITCH;
         const uint16_t* Os = Os0 + (i0 - t0) * C::PITCH;
@@ -454,8 +546,10 @@ static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B
     row_split(T, &nblk, &nw);
     const int trows = tile_rows<DHP>(T);
     const size_t shmem = (size_t)2 * trows * AtCfg<DHP>::PITCH * sizeof(uint16_t);
-    RC_LDS(raise_lds(attn_fwd_mfma<DHP>, shmem));
-    hipLaunchKernelGGL((attn_fwd_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, lse, T, H, dh, trows);
+    // (the register prefetch of the streamed mode costs the forward kernel one resident wavefront per
+    // SIMD and measured slower there; the backward kernels gain 20 % from it)
+    RC_LDS(raise_lds(attn_fwd_mfma<DHP, false>, shmem));
+    hipLaunchKernelGGL((attn_fwd_mfma<DHP, false>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, lse, T, H, dh, trows);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
@@ -468,12 +562,19 @@ static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16*
     const int trows = tile_rows<DHP>(T);
     const size_t shmem = (size_t)2 * trows * AtCfg<DHP>::PITCH * sizeof(uint16_t);
     const size_t shmem2 = shmem + 2 * trows * sizeof(float);
-    RC_LDS(raise_lds(attn_bwd_dq_mfma<DHP>, shmem));
-    RC_LDS(raise_lds(attn_bwd_dkv_mfma<DHP>, shmem2));
-    hipLaunchKernelGGL((attn_bwd_dq_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, dout, lse, dqkv,
-                       delta, T, H, dh, trows);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP>), dim3(nblk, B * H), dim3(nw * 64), shmem2, s, qkv, dout, lse, delta,
-                       dqkv, T, H, dh, trows);
+    if (trows == AT_ROWS && nw >= 4) {          // streamed mode with register prefetch of the next tile
+        hipLaunchKernelGGL((attn_bwd_dq_mfma<DHP, true>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, dout, lse, dqkv,
+                           delta, T, H, dh, trows);
+        hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP, true>), dim3(nblk, B * H), dim3(nw * 64), shmem2, s, qkv, dout, lse, delta,
+                           dqkv, T, H, dh, trows);
+    } else {
+        RC_LDS(raise_lds(attn_bwd_dq_mfma<DHP, false>, shmem));
+        RC_LDS(raise_lds(attn_bwd_dkv_mfma<DHP, false>, shmem2));
+        hipLaunchKernelGGL((attn_bwd_dq_mfma<DHP, false>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, dout, lse, dqkv,
+                           delta, T, H, dh, trows);
+        hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP, false>), dim3(nblk, B * H), dim3(nw * 64), shmem2, s, qkv, dout, lse, delta,
+                           dqkv, T, H, dh, trows);
+    }
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
