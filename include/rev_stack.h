@@ -152,7 +152,10 @@ int rev_stack_backward_reprop(const rev_cfg* cfg, const void* params,
  * `stream_recompute` first
  * waits for everything already enqueued on `stream_grad` and is joined back
  * into `stream_grad` before the call returns.  The two streams must differ and
- * must have the same (default) priority. */
+ * must have the same (default) priority.  The call enqueues kernels and event
+ * records / waits only, so it may be issued while `stream_grad` is being
+ * captured into a HIP graph: `stream_recompute` joins the capture through the
+ * fork event and the graph replays the whole two-stream pass. */
 int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params,
                                 const float* Y1, const float* Y2,
                                 const float* dY1, const float* dY2,

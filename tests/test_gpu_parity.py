@@ -152,3 +152,38 @@ def test_reprop_in_its_smaller_workspace_gives_the_same_bits(name, mode):
     assert bool((buf[small:] == 0xA5).all()), "wrote past the small workspace"
     with pytest.raises(B.RevError, match="workspace too small"):
         B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side, workspace=ws_small)
+
+
+def test_pareprop_call_can_be_captured_into_a_graph_and_replayed():
+    """The two-stream call enqueues only kernels and event waits, so a caller may capture it into a
+    HIP graph (both streams join the capture through the call's own fork / join events).  Replays,
+    with eager work and a scrambled workspace in between, reproduce the eager bits."""
+    cfg = dict(SHAPES["ragged_dh64"], mode="bf16")
+    flat, blocks, x, dy1, dy2 = make_case(cfg, seed=7)
+    c = gpu_cfg(cfg)
+    params = to_dev(flat, B.param_dtype(c))
+    ws = B.alloc_workspace(c)
+    X, dY1, dY2 = to_dev(x), to_dev(dy1), to_dev(dy2)
+    Y1, Y2 = B.rev_stack_forward(c, params, X, X, workspace=ws)
+    side = torch.cuda.Stream()
+    out = {}
+    out.update(B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side, workspace=ws, want_inputs=True))
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in out.items()}
+    cap = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side, workspace=ws, want_inputs=True, out=out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for v in out.values():
+            v.zero_()
+        ws.fill_(0x7F)
+        eager = B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2)      # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ref:
+            assert torch.equal(out[k], ref[k]), (rep, k)
+            assert torch.equal(eager[k], ref[k]) if eager.get(k) is not None else True
