@@ -98,8 +98,8 @@ int64_t rev_stack_param_offset(const rev_cfg* cfg, int32_t block, int32_t tensor
  * Holds: two activation slots (the per-block intermediates a gradient step
  * consumes; the second slot is what lets block i-1 be recomputed while block i
  * is still being differentiated, Sec. 3.2/3.3), a ring of three residual-stream
- * levels, two cotangent levels, gradient temporaries, transposed weight copies
- * and the partial sums of the deterministic reductions.  Host only. */
+ * levels, two cotangent levels, gradient temporaries and the partial sums of
+ * the deterministic reductions.  Host only. */
 int64_t rev_stack_workspace_bytes(const rev_cfg* cfg);
 
 /* Bytes of the smaller workspace that rev_stack_forward and

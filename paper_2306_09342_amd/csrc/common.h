@@ -32,7 +32,7 @@ enum Kind {
     K_LN_BWD,
     K_COLSUM,        // bias gradients (column sums), first stage
     K_REDUCE,        // fixed-order second stage of column sums / split reductions
-    K_CONVERT,       // dtype conversion and weight transposes
+    K_CONVERT,       // dtype conversion
     K_OPTIM,         // optimizer update
     K_COUNT
 };
@@ -191,9 +191,6 @@ int reduce_rows2(hipStream_t s, const float* partial, int P, int64_t stride, int
                  int64_t split);
 
 int convert_f32_to_bf16(hipStream_t s, const float* in, bf16* out, int64_t n);
-int copy_f32(hipStream_t s, const float* in, float* out, int64_t n);
-// out[c, r] = in[r, c]  (in: [R, C] row-major)
-int transpose_bf16(hipStream_t s, const bf16* in, bf16* out, int R, int C);
 
 // ---- attention ----------------------------------------------------------------------
 // qkv [B*T, 3D] (q|k|v, head-major inside each), o [B*T, D], lse [B, H, T]

@@ -1,5 +1,5 @@
 // Memory-bound kernels: LayerNorm forward / backward, column sums, fixed-order
-// reductions, dtype conversion, transposes.  One wavefront (64 lanes) owns one
+// reductions, dtype conversion.  One wavefront (64 lanes) owns one
 // row at a time and keeps it in registers; row statistics are wavefront
 // reductions; column statistics (d gamma, d beta, bias gradients) are summed in
 // a fixed order so that results do not depend on scheduling.
@@ -473,7 +473,7 @@ int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, flo
 template int colsum<float>(hipStream_t, const float*, int64_t, int, int, float*, float*, RedSeg*);
 template int colsum<bf16>(hipStream_t, const bf16*, int64_t, int, int, float*, float*, RedSeg*);
 
-// ---- conversion, copy, transpose ------------------------------------------------------------
+// ---- conversion ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void cvt_kernel(const float* __restrict__ in, bf16* __restrict__ out, int64_t n4) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n4) store4(out + 4 * i, load4(in + 4 * i));
@@ -483,43 +483,6 @@ int convert_f32_to_bf16(hipStream_t s, const float* in, bf16* out, int64_t n) {
     ProfScope ps(K_CONVERT, s, (double)n * 6);
     int64_t n4 = n / 4;
     hipLaunchKernelGGL(cvt_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, in, out, n4);
-    REV_HIP(hipGetLastError());
-    return REV_OK;
-}
-
-__global__ __launch_bounds__(256) void copy_kernel(const float* __restrict__ in, float* __restrict__ out, int64_t n4) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n4) store4(out + 4 * i, load4(in + 4 * i));
-}
-int copy_f32(hipStream_t s, const float* in, float* out, int64_t n) {
-    if (n % 4 != 0) { set_error("copy: length must be a multiple of 4"); return REV_EINVAL; }
-    ProfScope ps(K_CONVERT, s, (double)n * 8);
-    int64_t n4 = n / 4;
-    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, in, out, n4);
-    REV_HIP(hipGetLastError());
-    return REV_OK;
-}
-
-__global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
-                                                        int R, int C) {
-    __shared__ uint16_t tile[64][66];
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4) {
-        int r = r0 + i, c = c0 + tx;
-        if (r < R && c < C) tile[i][tx] = in[(int64_t)r * C + c];
-    }
-    __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        int c = c0 + i, r = r0 + tx;
-        if (r < R && c < C) out[(int64_t)c * R + r] = tile[tx][i];
-    }
-}
-int transpose_bf16(hipStream_t s, const bf16* in, bf16* out, int R, int C) {
-    ProfScope ps(K_CONVERT, s, (double)R * C * 4);
-    dim3 grid((C + 63) / 64, (R + 63) / 64), block(256);
-    hipLaunchKernelGGL(transpose_kernel, grid, block, 0, s, reinterpret_cast<const uint16_t*>(in),
-                       reinterpret_cast<uint16_t*>(out), R, C);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
