@@ -184,12 +184,6 @@ template <typename T>
 int colsum(hipStream_t s, const T* in, int64_t ld, int M, int N, float* out, float* partial, RedSeg* defer = nullptr);
 int64_t colsum_partial_elems(int M, int N);
 
-// out[i] = sum_p partial[p * stride + i], p ascending
-int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out);
-// elements [0, split) go to out, [split, n) to out2 (nullable: dropped)
-int reduce_rows2(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out, float* out2,
-                 int64_t split);
-
 int convert_f32_to_bf16(hipStream_t s, const float* in, bf16* out, int64_t n);
 
 // ---- attention ----------------------------------------------------------------------

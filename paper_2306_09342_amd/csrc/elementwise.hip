@@ -366,17 +366,6 @@ int reduce_multi(hipStream_t s, const RedSeg* segs, int nseg) {
     return REV_OK;
 }
 
-int reduce_rows(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out) {
-    return reduce_rows2(s, partial, P, stride, n, out, nullptr, n);
-}
-
-// Elements [0, split) of the sum go to out, elements [split, n) to out2 (dropped if out2 is null).
-int reduce_rows2(hipStream_t s, const float* partial, int P, int64_t stride, int64_t n, float* out, float* out2,
-                 int64_t split) {
-    const RedSeg g = {partial, out, out2, stride, n, split, P};
-    return reduce_multi(s, &g, 1);
-}
-
 int64_t ln_bwd_partial_elems(int M, int D) {
     const int rpb = ln_bwd_rows_per_block(M);
     return (int64_t)((M + rpb - 1) / rpb) * 3 * D;
