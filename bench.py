@@ -370,8 +370,10 @@ def main():
 
     hidden = (float(np.median(ms_r)) - float(np.median(ms_p))) / float(np.median(ms_rc))
     line = {
-        "metric": "reversible backward samples/s (PaReprop schedule), Rev-ViT-B bs=64"
-                  if args.workload == "vit_b" else f"reversible backward samples/s (PaReprop schedule), {args.workload}",
+        # the headline metric as named for this path: `value` is the PaReprop schedule's samples/s, the Reprop
+        # figure and the matrix-core fractions are on the same line ("reprop", "mfma_fraction_whole_path", "roofline")
+        "metric": "reversible backward samples/s (PaReprop vs Reprop), Rev-ViT-B bs=64; MFMA util"
+                  if args.workload == "vit_b" else f"reversible backward samples/s (PaReprop vs Reprop), {args.workload}; MFMA util",
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["mode"], "data": "synthetic",
