@@ -559,7 +559,10 @@ static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16*
                       float* delta, int B, int T, int H, int dh) {
     int nblk, nw;
     row_split(T, &nblk, &nw);
-    const int trows = tile_rows<DHP>(T);
+    // With 4 or more wavefronts the backward kernels always stream 64-row tiles with the next tile
+    // prefetched into registers: measured 6-8 % faster than keeping the head resident (197 and 257
+    // tokens), with a fifth of the LDS, which also leaves room for a co-running kernel of the other stream.
+    const int trows = (nw >= 4) ? AT_ROWS : tile_rows<DHP>(T);
     const size_t shmem = (size_t)2 * trows * AtCfg<DHP>::PITCH * sizeof(uint16_t);
     const size_t shmem2 = shmem + 2 * trows * sizeof(float);
     if (trows == AT_ROWS && nw >= 4) {          // streamed mode with register prefetch of the next tile
