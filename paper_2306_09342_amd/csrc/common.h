@@ -126,6 +126,8 @@ struct Epi {
     int64_t ldo;
     float* colsum;      // EPI_GELU_BWD, matrix-core path: per-row-strip column sums of the output,
                         // [gemm_colsum_rows(M)][N] float32 (nullable)
+    bool solo;          // the launch runs alone on the device (one stream): the tile shape may be chosen
+                        // to fill the chip by itself; results do not depend on it
 };
 // 64-row strips of column-sum partials the matrix-core GEMM writes for M rows, and an upper bound for sizing
 int gemm_colsum_strips(int M);

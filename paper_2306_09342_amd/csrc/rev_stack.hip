@@ -232,11 +232,13 @@ struct Runner {
     const T* params;
     float* dparams;
     int M, D, Dm, H, dh, B, Tn;
+    bool solo;      // one stream: every kernel has the device to itself
 
     Runner(const rev_cfg& cfg, const void* p, float* dp, void* w, bool compact)
-        : c(cfg), L(make_layout(cfg, compact)), ws((char*)w), params((const T*)p), dparams(dp) {
+        : c(cfg), L(make_layout(cfg, compact)), ws((char*)w), params((const T*)p), dparams(dp), solo(compact) {
         M = c.batch * c.seq_len; D = c.d_model; Dm = c.d_mlp; H = c.n_heads; dh = D / H; B = c.batch; Tn = c.seq_len;
     }
+    Epi epi0() const { Epi e = {}; e.solo = solo; return e; }
     template <typename U> U* at(int64_t off) const { return reinterpret_cast<U*>(ws + off); }
     const T* P(int blk, int t) const { return params + (int64_t)blk * block_params(c) + tensor_offset(c, t); }
     float* G(int blk, int t) const { return dparams + (int64_t)blk * block_params(c) + tensor_offset(c, t); }
@@ -250,22 +252,22 @@ struct Runner {
     // F branch pieces up to the projection input: n1, qkv, o, lse from x2
     int f_pre(hipStream_t s, int blk, const float* x2, const Slot& sl) {
         RC((ln_forward<T, T>(s, x2, P(blk, T_LN1G), P(blk, T_LN1B), c.ln_eps, sl.n1, sl.st1, M, D)));
-        Epi e = {}; e.kind = EPI_BIAS; e.out = sl.qkv; e.bias = P(blk, T_BQKV); e.ldo = 3 * D;
+        Epi e = epi0(); e.kind = EPI_BIAS; e.out = sl.qkv; e.bias = P(blk, T_BQKV); e.ldo = 3 * D;
         RC(Ops<T>::nt(s, sl.n1, D, P(blk, T_WQKV), D, M, 3 * D, D, e));
         RC((attention_forward<T>(s, sl.qkv, sl.o, sl.lse, B, Tn, H, dh)));
         return REV_OK;
     }
     // out1 = in1 + sign * (o Wp^T + bp)
     int f_post(hipStream_t s, int blk, const Slot& sl, const float* in1, float* out1, float sign) {
-        Epi e = {}; e.kind = EPI_RESIDUAL; e.outf = out1; e.res = in1; e.bias = P(blk, T_BPROJ); e.sign = sign; e.ldo = D;
+        Epi e = epi0(); e.kind = EPI_RESIDUAL; e.outf = out1; e.res = in1; e.bias = P(blk, T_BPROJ); e.sign = sign; e.ldo = D;
         return Ops<T>::nt(s, sl.o, D, P(blk, T_WPROJ), D, M, D, D, e);
     }
     // out2 = in2 + sign * G(y1)
     int g_branch(hipStream_t s, int blk, const float* y1, const Slot& sl, const float* in2, float* out2, float sign) {
         RC((ln_forward<T, T>(s, y1, P(blk, T_LN2G), P(blk, T_LN2B), c.ln_eps, sl.n2, sl.st2, M, D)));
-        Epi e = {}; e.kind = EPI_BIAS_GELU; e.out = sl.h; e.out2 = sl.a; e.bias = P(blk, T_BFC1); e.ldo = Dm;
+        Epi e = epi0(); e.kind = EPI_BIAS_GELU; e.out = sl.h; e.out2 = sl.a; e.bias = P(blk, T_BFC1); e.ldo = Dm;
         RC(Ops<T>::nt(s, sl.n2, D, P(blk, T_WFC1), D, M, Dm, D, e));
-        Epi r = {}; r.kind = EPI_RESIDUAL; r.outf = out2; r.res = in2; r.bias = P(blk, T_BFC2); r.sign = sign; r.ldo = D;
+        Epi r = epi0(); r.kind = EPI_RESIDUAL; r.outf = out2; r.res = in2; r.bias = P(blk, T_BFC2); r.sign = sign; r.ldo = D;
         return Ops<T>::nt(s, sl.a, Dm, P(blk, T_WFC2), Dm, M, D, Dm, r);
     }
 
@@ -321,7 +323,7 @@ struct Runner {
 
         // ---- G branch: dh = (dY2 W2) * gelu'(h); the bias gradient of fc1 (column sums of dh) rides
         // in the epilogue of the matrix-core kernel, otherwise it is a separate pass
-        Epi e = {}; e.kind = EPI_GELU_BWD; e.out = dhb; e.aux = sl.h; e.ldo = Dm;
+        Epi e = epi0(); e.kind = EPI_GELU_BWD; e.out = dhb; e.aux = sl.h; e.ldo = Dm;
         bool fused_db1 = false;
         if constexpr (kBf16) fused_db1 = gemm_bf16_fast_path(d2b, D, P(blk, T_WFC2), Dm, Dm, D, e);
         if (fused_db1) e.colsum = pcol0;
@@ -329,18 +331,18 @@ struct Runner {
         if (ev) REV_HIP(hipEventRecord(ev[0], s));
         if (fused_db1) segs[nseg++] = {pcol0, G(blk, T_BFC1), nullptr, (int64_t)Dm, (int64_t)Dm, (int64_t)Dm, gemm_colsum_strips(M)};
         else RC(colsum<T>(s, dhb, Dm, M, Dm, G(blk, T_BFC1), pcol0, &segs[nseg++]));
-        Epi p = {}; p.kind = EPI_PLAIN; p.out = dn; p.ldo = D;
+        Epi p = epi0(); p.kind = EPI_PLAIN; p.out = dn; p.ldo = D;
         RC(dgrad(s, blk, T_WFC1, dhb, Dm, D, p));
         // gY1 = dY1 + LN2bwd(dn); its column sums are the bias gradient of the projection
         RC((ln_backward<T, T>(s, dn, y1, sl.st2, P(blk, T_LN2G), d1, o1, kBf16 ? gy1b : nullptr,
                               G(blk, T_LN2G), G(blk, T_BPROJ), at<float>(L.part_ln[0]), M, D, &segs[nseg++])));
         if (ev) REV_HIP(hipEventRecord(ev[1], s));
         // ---- F branch
-        Epi q = {}; q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
+        Epi q = epi0(); q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
         RC(dgrad(s, blk, T_WPROJ, gy1b, D, D, q));
         RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh)));
         if (ev) REV_HIP(hipEventRecord(ev[2], s));
-        Epi r = {}; r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
+        Epi r = epi0(); r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
         RC(dgrad(s, blk, T_WQKV, dqkv, 3 * D, D, r));
         RC(colsum<T>(s, dqkv, 3 * D, M, 3 * D, G(blk, T_BQKV), pcol1, &segs[nseg++]));
         // dX2 = dY2 + LN1bwd(dn); dX2 is the block below's dY2, so its column sums are that block's
