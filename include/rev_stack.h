@@ -107,7 +107,7 @@ int64_t rev_stack_workspace_bytes(const rev_cfg* cfg);
  * produced while block i is still being consumed, so ONE activation slot, two
  * residual-stream levels and single gradient temporaries suffice.  The
  * difference to rev_stack_workspace_bytes is the extra memory the parallel
- * schedule pays for its speed (Sec. 3.3; memory trends, Sec. 5.2).  Host only. */
+ * schedule pays for its speed (Sec. 3.3; memory trends, Sec. 4.2).  Host only. */
 int64_t rev_stack_workspace_bytes_reprop(const rev_cfg* cfg);
 
 /* Bytes of one activation slot: the intermediates of ONE block that a gradient
@@ -115,7 +115,7 @@ int64_t rev_stack_workspace_bytes_reprop(const rev_cfg* cfg);
  * MLP pre-activation and activation).  Backpropagation without recomputation
  * would keep one such slot, plus both residual streams, per block; the
  * reversible schedules keep one (Reprop) or two (PaReprop) in total.  For the
- * memory-versus-batch comparison of Sec. 5.2.  Host only. */
+ * memory-versus-batch comparison of Sec. 4.2.  Host only. */
 int64_t rev_stack_slot_bytes(const rev_cfg* cfg);
 
 /* Forward map of the whole stack (Eq. 1 applied N times); stores no
@@ -165,7 +165,7 @@ int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params,
                                 void* stream_grad, void* stream_recompute);
 
 /* Optimizer update of a training step: AdamW, the optimizer of the paper's
- * throughput experiments (Sec. 5, experimental setup; the paper gives neither
+ * throughput experiments (Sec. 4, experimental setup; the paper gives neither
  * formula nor hyper-parameters, so this is the published update with decoupled
  * weight decay, eps outside the square root, step counter from 1):
  *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;

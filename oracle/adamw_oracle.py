@@ -1,6 +1,6 @@
 """CPU oracle for the optimizer update of a training step -- TEST INFRASTRUCTURE ONLY.
 
-The paper trains with AdamW (Sec. 5, experimental setup) and also reports that
+The paper trains with AdamW (Sec. 4, experimental setup) and also reports that
 plain SGD behaves alike; it gives no hyper-parameters and no formula, so the
 update is the published one (Adam with decoupled weight decay), written out
 here in float64, one line per quantity, no fusion:

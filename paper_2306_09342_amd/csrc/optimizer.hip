@@ -1,5 +1,5 @@
 // Optimizer update of a training step: AdamW (Adam with decoupled weight decay), the optimizer the
-// paper's throughput experiments train with (Sec. 5).  One pass over the packed parameter vector:
+// paper's throughput experiments train with (Sec. 4).  One pass over the packed parameter vector:
 // float32 master weights, float32 moments and the float32 gradient in, master weights and moments
 // out, plus (bf16 mode) the bf16 copy the stack's kernels read.  Purely HBM-bound: 16 bytes read and
 // 12 (14) written per element, nothing reused, so the kernel is a grid-stride loop of 16-byte accesses.

@@ -115,7 +115,7 @@ struct Layout {
 // compact = the layout of the sequential schedule (and of the forward map): nothing of block i-1
 // is produced while block i is still being consumed, so one activation slot, two residual levels and
 // one copy of each per-block gradient temporary are enough.  The full layout doubles those, which is
-// the extra memory the parallel schedule pays (Sec. 3.3, Sec. 5.2).
+// the extra memory the parallel schedule pays (Sec. 3.3, Sec. 4.2).
 static Layout make_layout(const rev_cfg& c, bool compact) {
     Layout L = {};
     const int64_t M = (int64_t)c.batch * c.seq_len, D = c.d_model, Dm = c.d_mlp;

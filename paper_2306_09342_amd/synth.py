@@ -26,14 +26,14 @@ CONFIGS = {
     "vit_b": dict(n_blocks=12, d_model=768, n_heads=12, d_mlp=3072, seq_len=197, batch=64, mode="bf16"),
     "roberta_base": dict(n_blocks=12, d_model=768, n_heads=12, d_mlp=3072, seq_len=512, batch=32, mode="bf16"),
     "vit_h": dict(n_blocks=32, d_model=1280, n_heads=16, d_mlp=5120, seq_len=257, batch=32, mode="bf16"),
-    # further text-model points of the paper's sequence-length / model-size comparison (Sec. 5.1, NLP):
+    # further text-model points of the paper's sequence-length / model-size comparison (Sec. 4.1, NLP):
     # the base width at 1024 tokens and the large width (24 blocks, 1024 wide, 16 heads) at 512 and 1024
     "roberta_base_t1024": dict(n_blocks=12, d_model=768, n_heads=12, d_mlp=3072, seq_len=1024, batch=16, mode="bf16"),
     "roberta_large": dict(n_blocks=24, d_model=1024, n_heads=16, d_mlp=4096, seq_len=512, batch=16, mode="bf16"),
     "roberta_large_t1024": dict(n_blocks=24, d_model=1024, n_heads=16, d_mlp=4096, seq_len=1024, batch=8, mode="bf16"),
 }
 
-# Hierarchical (window-attention) workloads, Sec. 4 / Sec. 5.1: a list of stages, each a homogeneous
+# Hierarchical (window-attention) workloads, Sec. 3.4 / Sec. 4.1: a list of stages, each a homogeneous
 # reversible stack whose "samples" are the attention windows of the images.  224 x 224 inputs, 4 x 4
 # patches, 7 x 7 windows: 49 tokens per window and 64 / 16 / 4 / 1 windows per image in the four
 # stages, width doubling and head count doubling from stage to stage (head_dim 32), MLP ratio 4.

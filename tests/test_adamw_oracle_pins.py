@@ -1,6 +1,6 @@
 """Pins of the optimizer oracle (oracle/adamw_oracle.py) against things other
 than itself: torch's own AdamW run in float64, and closed forms that follow from
-the update rule (Adam with decoupled weight decay; the paper, Sec. 5, only names
+the update rule (Adam with decoupled weight decay; the paper, Sec. 4, only names
 the optimizer)."""
 import numpy as np
 import torch
