@@ -198,6 +198,55 @@ int rev_stack_backward_chain(const rev_cfg* cfg, const void* params,
                              void* workspace, int64_t workspace_bytes,
                              void* stream, int32_t chain);
 
+/* ---- Stage transition of a hierarchical reversible model ------------------
+ *
+ * Between two stages of its hierarchical (window-attention) model the paper
+ * places a block that first fuses the two residual streams (by averaging, or
+ * by a small MLP) and then applies the usual patch merging (Sec. 3.4 and
+ * panel (b) of the architecture figure).  The reading built here: fusion by
+ * averaging; patch merging = concatenate every 2x2 neighbourhood of the token
+ * grid along the feature axis (C -> 4C, neighbour (dy, dx) at feature block
+ * 2*dy + dx), LayerNorm over the 4C features, bias-free linear map 4C -> 2C;
+ * both streams of the next stage start from the result, so the backward pass
+ * takes one cotangent per copy and adds them.  The block is not reversible:
+ * the caller keeps its inputs (the last stage's outputs) for the backward call.
+ *
+ * Tokens are stored window by window, on both sides: row
+ *   ((b * (grid_h/window) + y/window) * (grid_w/window) + x/window) * window^2
+ *     + (y % window) * window + (x % window)
+ * holds the token at grid position (y, x) of image b, so that a stage's
+ * windows are the contiguous sequences rev_stack_* works on.  The merged map
+ * has (grid_h/2) x (grid_w/2) tokens per image in the same order.
+ *
+ * Packed parameters (element type as in rev_cfg.mode): ln_gamma[4C],
+ * ln_beta[4C], W[2C, 4C] row-major.  dparams: same layout, float32,
+ * overwritten.  X1, X2, dX1, dX2: [batch*grid_h*grid_w, C] float32.  out, dOutA,
+ * dOutB: [batch*grid_h*grid_w/4, 2C] float32.  All device pointers, 16-byte
+ * aligned; the workspace 256-byte aligned and at least
+ * rev_merge_workspace_bytes() long.  Calls enqueue on `stream` and return;
+ * nothing is allocated.  Errors as for the rev_stack_* calls. */
+typedef struct rev_merge_cfg {
+    int32_t batch;      /* images                                              */
+    int32_t grid_h;     /* token grid of the incoming stage; both sides must   */
+    int32_t grid_w;     /*   be multiples of 2 * window                        */
+    int32_t window;     /* side of the square attention windows                */
+    int32_t d_in;       /* width C of the incoming stage (multiple of 8, <= 2048) */
+    int32_t mode;       /* REV_MODE_FP32 or REV_MODE_BF16                      */
+    float   ln_eps;
+} rev_merge_cfg;
+
+int     rev_merge_check_cfg(const rev_merge_cfg* cfg);
+int64_t rev_merge_param_count(const rev_merge_cfg* cfg);      /* 8C + 8C^2 */
+int64_t rev_merge_workspace_bytes(const rev_merge_cfg* cfg);
+int rev_merge_forward(const rev_merge_cfg* cfg, const void* params,
+                      const float* X1, const float* X2, float* out,
+                      void* workspace, int64_t workspace_bytes, void* stream);
+int rev_merge_backward(const rev_merge_cfg* cfg, const void* params,
+                       const float* X1, const float* X2,
+                       const float* dOutA, const float* dOutB,
+                       float* dX1, float* dX2, float* dparams,
+                       void* workspace, int64_t workspace_bytes, void* stream);
+
 /* Per-kernel-family timing.  Between rev_profile_begin() and rev_profile_end()
  * every kernel launch made by the calling process is bracketed by a pair of
  * HIP events on the stream it is launched on.  rev_profile_end() synchronises

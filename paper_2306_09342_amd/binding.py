@@ -24,6 +24,7 @@ EXPORTS = (
     "rev_stack_workspace_bytes_reprop", "rev_stack_slot_bytes",
     "rev_stack_forward", "rev_stack_backward_reprop", "rev_stack_backward_pareprop", "rev_stack_backward_chain",
     "rev_adamw_step",
+    "rev_merge_check_cfg", "rev_merge_param_count", "rev_merge_workspace_bytes", "rev_merge_forward", "rev_merge_backward",
     "rev_profile_begin", "rev_profile_end", "rev_profile_kinds", "rev_profile_name", "rev_profile_is_flops",
     "rev_profile_get", "rev_last_error",
 )
@@ -33,6 +34,12 @@ class RevCfg(ctypes.Structure):
     _fields_ = [("n_blocks", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32),
                 ("d_mlp", ctypes.c_int32), ("seq_len", ctypes.c_int32), ("batch", ctypes.c_int32),
                 ("mode", ctypes.c_int32), ("ln_eps", ctypes.c_float)]
+
+
+class RevMergeCfg(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
+                ("window", ctypes.c_int32), ("d_in", ctypes.c_int32), ("mode", ctypes.c_int32),
+                ("ln_eps", ctypes.c_float)]
 
 
 class RevError(RuntimeError):
@@ -72,6 +79,16 @@ def lib():
         f32 = ctypes.c_float
         L.rev_adamw_step.argtypes = [i64, vp, vp, vp, vp, vp, i32, f32, f32, f32, f32, f32, vp]
         L.rev_adamw_step.restype = ctypes.c_int
+        mp = ctypes.POINTER(RevMergeCfg)
+        L.rev_merge_check_cfg.argtypes = [mp]
+        L.rev_merge_check_cfg.restype = ctypes.c_int
+        for n in ("rev_merge_param_count", "rev_merge_workspace_bytes"):
+            getattr(L, n).argtypes = [mp]
+            getattr(L, n).restype = i64
+        L.rev_merge_forward.argtypes = [mp, vp, vp, vp, vp, vp, i64, vp]
+        L.rev_merge_forward.restype = ctypes.c_int
+        L.rev_merge_backward.argtypes = [mp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+        L.rev_merge_backward.restype = ctypes.c_int
         for n in ("rev_profile_begin", "rev_profile_end", "rev_profile_kinds"):
             getattr(L, n).argtypes = []
             getattr(L, n).restype = ctypes.c_int
@@ -224,6 +241,65 @@ def rev_adamw_step(master, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-
         assert params_bf16.numel() == master.numel()
     _check(lib().rev_adamw_step(master.numel(), _ptr(master), _ptr(params_bf16), _ptr(grad), _ptr(m), _ptr(v),
                                 int(step), lr, beta1, beta2, eps, weight_decay, _stream_handle(stream)))
+
+
+def make_merge_cfg(batch, grid_h, grid_w, window, d_in, mode="bf16", ln_eps=1e-5) -> RevMergeCfg:
+    m = MODES[mode] if isinstance(mode, str) else int(mode)
+    return RevMergeCfg(batch, grid_h, grid_w, window, d_in, m, ln_eps)
+
+
+def rev_merge_check_cfg(cfg: RevMergeCfg) -> int:
+    return lib().rev_merge_check_cfg(ctypes.byref(cfg))
+
+
+def rev_merge_param_count(cfg: RevMergeCfg) -> int:
+    return _check(lib().rev_merge_param_count(ctypes.byref(cfg)))
+
+
+def rev_merge_workspace_bytes(cfg: RevMergeCfg) -> int:
+    return _check(lib().rev_merge_workspace_bytes(ctypes.byref(cfg)))
+
+
+def _merge_shapes(cfg):
+    m_in = cfg.batch * cfg.grid_h * cfg.grid_w
+    return (m_in, cfg.d_in), (m_in // 4, 2 * cfg.d_in)
+
+
+def rev_merge_forward(cfg, params, X1, X2, workspace=None, stream=None, out=None):
+    """Stage transition: average of the two streams, 2x2 patch merging, LayerNorm, linear map 4C -> 2C."""
+    s_in, s_out = _merge_shapes(cfg)
+    _want(params, param_dtype(cfg), (rev_merge_param_count(cfg),))
+    _want(X1, torch.float32, s_in)
+    _want(X2, torch.float32, s_in)
+    out = torch.empty(s_out, dtype=torch.float32, device=X1.device) if out is None else out
+    _want(out, torch.float32, s_out)
+    ws = torch.empty(rev_merge_workspace_bytes(cfg), dtype=torch.uint8, device=X1.device) if workspace is None else workspace
+    _check(lib().rev_merge_forward(ctypes.byref(cfg), _ptr(params), _ptr(X1), _ptr(X2), _ptr(out), _ptr(ws), ws.numel(),
+                                   _stream_handle(stream)))
+    return out
+
+
+def rev_merge_backward(cfg, params, X1, X2, dOutA, dOutB, workspace=None, stream=None, out=None):
+    """Backward of the stage transition; dOutA and dOutB are the cotangents of the two copies of its output."""
+    s_in, s_out = _merge_shapes(cfg)
+    _want(params, param_dtype(cfg), (rev_merge_param_count(cfg),))
+    for t in (X1, X2):
+        _want(t, torch.float32, s_in)
+    for t in (dOutA, dOutB):
+        _want(t, torch.float32, s_out)
+    out = {} if out is None else out
+    dX1 = out.get("dX1")
+    dX1 = torch.empty_like(X1) if dX1 is None else dX1
+    dX2 = out.get("dX2")
+    dX2 = torch.empty_like(X1) if dX2 is None else dX2
+    dparams = out.get("dparams")
+    dparams = torch.empty(params.numel(), dtype=torch.float32, device=X1.device) if dparams is None else dparams
+    for t, shp in ((dX1, s_in), (dX2, s_in), (dparams, (params.numel(),))):
+        _want(t, torch.float32, shp)
+    ws = torch.empty(rev_merge_workspace_bytes(cfg), dtype=torch.uint8, device=X1.device) if workspace is None else workspace
+    _check(lib().rev_merge_backward(ctypes.byref(cfg), _ptr(params), _ptr(X1), _ptr(X2), _ptr(dOutA), _ptr(dOutB),
+                                    _ptr(dX1), _ptr(dX2), _ptr(dparams), _ptr(ws), ws.numel(), _stream_handle(stream)))
+    return {"dX1": dX1, "dX2": dX2, "dparams": dparams}
 
 
 def rev_profile_begin():

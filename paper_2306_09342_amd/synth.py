@@ -125,3 +125,37 @@ def make_inputs(cfg: dict, seed: int = 0, batch: int | None = None):
         rng = np.random.default_rng([seed, 7, tid])
         out.append(rng.standard_normal((B, T, D), dtype=np.float32))
     return tuple(out)
+
+
+# Stage transitions of the hierarchical workloads (Sec. 3.4): between stage s and s+1 of a hierarchy the
+# token grid halves per side and the width doubles.  Seeded inputs only; no arithmetic of the block here.
+def merge_cfgs(hier: dict, image: int = 224, patch: int = 4, window: int = 7):
+    """One dict per transition of HIERARCHIES[...]: batch (images), grid_h, grid_w, window, d_in, mode."""
+    out = []
+    for s, st in enumerate(hier["stages"][:-1]):
+        side = image // patch >> s
+        out.append(dict(batch=hier["images"], grid_h=side, grid_w=side, window=window, d_in=st["d_model"],
+                        mode=st["mode"], ln_eps=1e-5))
+    return out
+
+
+def make_merge_params(mcfg: dict, seed: int = 0, perturb: bool = False) -> np.ndarray:
+    """Packed float32 parameters of one transition: ln_gamma[4C], ln_beta[4C], W[2C, 4C]."""
+    C = mcfg["d_in"]
+    rng = np.random.default_rng([seed, 31, C])
+    g = 1.0 + (0.1 * rng.standard_normal(4 * C) if perturb else np.zeros(4 * C))
+    b = 0.1 * rng.standard_normal(4 * C) if perturb else np.zeros(4 * C)
+    w = _trunc_normal(rng, (2 * C, 4 * C), 0.02)
+    flat = np.concatenate([g, b, w.ravel()]).astype(np.float32)
+    if mcfg.get("mode", "fp32") == "bf16":
+        flat = to_bf16_grid(flat)
+    return flat
+
+
+def make_merge_inputs(mcfg: dict, seed: int = 0):
+    """Returns (X1, X2, dOutA, dOutB): float32 [B*Gh*Gw, C] twice and [B*Gh*Gw/4, 2C] twice."""
+    M = mcfg["batch"] * mcfg["grid_h"] * mcfg["grid_w"]
+    C = mcfg["d_in"]
+    shapes = [(M, C), (M, C), (M // 4, 2 * C), (M // 4, 2 * C)]
+    return tuple(np.random.default_rng([seed, 33, tid]).standard_normal(shp, dtype=np.float32)
+                 for tid, shp in enumerate(shapes))

@@ -128,3 +128,29 @@ def test_adamw_arguments_are_validated_before_any_gpu_work():
         args[idx] = val
         assert L.rev_adamw_step(*args) == -1, (idx, val)
         assert "adamw" in B.rev_last_error()
+
+
+def test_merge_cfg_validation_and_sizes():
+    ok = B.make_merge_cfg(4, 56, 56, 7, 96, "bf16")
+    assert B.rev_merge_check_cfg(ok) == 0
+    assert B.rev_merge_param_count(ok) == 8 * 96 + 8 * 96 * 96
+    # the workspace holds at least the normalised rows, the statistics and the two activation-typed cotangents
+    mo = 4 * 28 * 28
+    assert B.rev_merge_workspace_bytes(ok) >= mo * (4 * 96 * 2 * 2 + 2 * 96 * 2 + 8)
+    for bad in (B.make_merge_cfg(4, 56, 49, 7, 96), B.make_merge_cfg(4, 56, 56, 7, 100), B.make_merge_cfg(0, 56, 56, 7, 96),
+                B.make_merge_cfg(4, 56, 56, 7, 96, 7), B.make_merge_cfg(4, 56, 56, 7, 4096)):
+        assert B.rev_merge_check_cfg(bad) < 0
+        assert B.rev_last_error() != ""
+        with pytest.raises(B.RevError):
+            B.rev_merge_param_count(bad)
+
+
+def test_merge_calls_validate_before_touching_the_device():
+    c = B.make_merge_cfg(1, 14, 14, 7, 32, "fp32")
+    L = B.lib()
+    import ctypes
+    # null pointers and a short workspace are refused on the host
+    assert L.rev_merge_forward(ctypes.byref(c), None, None, None, None, None, 0, None) < 0
+    assert L.rev_merge_backward(ctypes.byref(c), None, None, None, None, None, None, None, None, None, 0, None) < 0
+    fake = ctypes.c_void_p(256)
+    assert L.rev_merge_forward(ctypes.byref(c), fake, fake, fake, fake, fake, 16, None) == -2
