@@ -117,37 +117,68 @@ def sweep_batch(args, cfg, B, synth, torch, np):
 
 
 def bench_hierarchy(args, hier, B, synth, torch, np):
-    """Hierarchical (window-attention shaped) workload: one step is the reversible backward pass of
-    every stage, last stage first, each stage a homogeneous stack over its attention windows."""
+    """Hierarchical (window-attention shaped) workload.  One step is the backward pass of the whole
+    hierarchy, last stage first: the reversible backward of a stage's stack over its attention windows,
+    then the backward of the stage transition below it (stream averaging + patch merging), whose input
+    cotangents are the output cotangents of the next stack.  The stage outputs the transitions need are
+    kept from one untimed forward pass, as a training step would have them."""
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     main_s = torch.cuda.current_stream()
     side = torch.cuda.Stream()
     stages = []
+    merges = []
+    mcfgs = synth.merge_cfgs(hier)
+    X1 = X2 = None
     for si, cfg in enumerate(hier["stages"]):
         c = B.make_cfg(**cfg)
         params = torch.from_numpy(synth.make_params(cfg, seed=si)).cuda().to(B.param_dtype(c))
-        x, dy1, dy2 = synth.make_inputs(cfg, seed=si)
-        X, dY1, dY2 = (torch.from_numpy(a).cuda() for a in (x, dy1, dy2))
+        shape = (cfg["batch"], cfg["seq_len"], cfg["d_model"])
+        if si == 0:
+            x, _, _ = synth.make_inputs(cfg, seed=si)
+            X1 = X2 = torch.from_numpy(x).cuda()
         ws = B.alloc_workspace(c)
-        Y1, Y2 = B.rev_stack_forward(c, params, X, X, workspace=ws)
+        Y1, Y2 = B.rev_stack_forward(c, params, X1.view(shape), X2.view(shape), workspace=ws)
         out = {}
-        out.update(B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws))
-        stages.append(dict(cfg=cfg, c=c, params=params, Y1=Y1, Y2=Y2, dY1=dY1, dY2=dY2, ws=ws, out=out))
-        del X
+        st = dict(cfg=cfg, c=c, params=params, Y1=Y1, Y2=Y2, ws=ws, out=out)
+        stages.append(st)
+        if si + 1 < len(hier["stages"]):
+            mc = B.make_merge_cfg(**mcfgs[si])
+            mp = torch.from_numpy(synth.make_merge_params(mcfgs[si], seed=si)).cuda().to(B.param_dtype(mc))
+            mws = torch.empty(B.rev_merge_workspace_bytes(mc), dtype=torch.uint8, device="cuda")
+            rows = cfg["batch"] * cfg["seq_len"]
+            merged = B.rev_merge_forward(mc, mp, Y1.view(rows, -1), Y2.view(rows, -1), workspace=mws)
+            merges.append(dict(c=mc, params=mp, ws=mws, out={}, rows=rows))
+            X1 = X2 = merged
+    # cotangents of the last stage's outputs
+    _, dy1, dy2 = synth.make_inputs(hier["stages"][-1], seed=len(stages) - 1)
+    top = (torch.from_numpy(dy1).cuda(), torch.from_numpy(dy2).cuda())
     torch.cuda.synchronize()
 
-    def run(schedule, only=None):
+    def stage_backward(si, schedule, dY1, dY2):
+        st = stages[si]
+        if schedule == "pareprop":
+            return B.rev_stack_backward_pareprop(st["c"], st["params"], st["Y1"], st["Y2"], dY1, dY2, side,
+                                                 workspace=st["ws"], out=st["out"])
+        return B.rev_stack_backward_reprop(st["c"], st["params"], st["Y1"], st["Y2"], dY1, dY2,
+                                           workspace=st["ws"], out=st["out"])
+
+    def merge_backward(mi, dA, dB):
+        m, below = merges[mi], stages[mi]
+        rows = m["rows"]
+        return B.rev_merge_backward(m["c"], m["params"], below["Y1"].view(rows, -1), below["Y2"].view(rows, -1),
+                                    dA.view(rows // 4, -1), dB.view(rows // 4, -1), workspace=m["ws"], out=m["out"])
+
+    def run(schedule):
+        dY1, dY2 = top
         for si in reversed(range(len(stages))):
-            if only is not None and si != only:
-                continue
-            st = stages[si]
-            if schedule == "pareprop":
-                B.rev_stack_backward_pareprop(st["c"], st["params"], st["Y1"], st["Y2"], st["dY1"], st["dY2"], side,
-                                              workspace=st["ws"], out=st["out"])
-            else:
-                B.rev_stack_backward_reprop(st["c"], st["params"], st["Y1"], st["Y2"], st["dY1"], st["dY2"],
-                                            workspace=st["ws"], out=st["out"])
+            res = stage_backward(si, schedule, dY1, dY2)
+            stages[si]["out"].update(res)
+            if si > 0:
+                mres = merge_backward(si - 1, res["dX1"], res["dX2"])
+                merges[si - 1]["out"].update(mres)
+                shape = stages[si - 1]["Y1"].shape
+                dY1, dY2 = mres["dX1"].view(shape), mres["dX2"].view(shape)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -167,34 +198,53 @@ def bench_hierarchy(args, hier, B, synth, torch, np):
 
     wall_p, ms_p = timed(lambda: run("pareprop"), args.steps, args.warmup)
     wall_r, ms_r = timed(lambda: run("reprop"), args.steps, args.warmup)
+    finite = all(bool(torch.isfinite(st["out"]["dparams"]).all()) for st in stages) and \
+        all(bool(torch.isfinite(m["out"]["dparams"]).all()) for m in merges)
+    # per-stage and per-transition times, each run alone with the cotangents the full pass left behind
+    grads_in = []
+    for si in range(len(stages)):
+        if si + 1 == len(stages):
+            grads_in.append(top)
+        else:
+            shape = stages[si]["Y1"].shape
+            grads_in.append((merges[si]["out"]["dX1"].clone().view(shape), merges[si]["out"]["dX2"].clone().view(shape)))
     per_stage = []
+    few = max(5, args.steps // 3)
     for si, st in enumerate(stages):
-        _, a = timed(lambda: run("pareprop", si), max(5, args.steps // 3), 2)
-        _, b = timed(lambda: run("reprop", si), max(5, args.steps // 3), 2)
+        d1, d2 = grads_in[si]
+        _, a = timed(lambda: stage_backward(si, "pareprop", d1, d2), few, 2)
+        _, b = timed(lambda: stage_backward(si, "reprop", d1, d2), few, 2)
         cfg = st["cfg"]
         B.rev_profile_begin()
         for _ in range(3):
-            run("reprop", si)
+            stage_backward(si, "reprop", d1, d2)
         fam = {k: round(ms / 3, 4) for k, (ms, n, work, is_flops) in B.rev_profile_end().items() if n}
-        per_stage.append({"stage": si + 1, "family_ms": fam, "blocks": cfg["n_blocks"], "d_model": cfg["d_model"], "windows": cfg["batch"],
-                          "tokens": cfg["seq_len"], "pareprop_ms": float(np.median(a)), "reprop_ms": float(np.median(b)),
-                          "algorithmic_tflop": algorithmic_flops(cfg) / 1e12})
+        entry = {"stage": si + 1, "family_ms": fam, "blocks": cfg["n_blocks"], "d_model": cfg["d_model"], "windows": cfg["batch"],
+                 "tokens": cfg["seq_len"], "pareprop_ms": float(np.median(a)), "reprop_ms": float(np.median(b)),
+                 "algorithmic_tflop": algorithmic_flops(cfg) / 1e12}
+        if si > 0:
+            dA, dB = st["out"]["dX1"].clone(), st["out"]["dX2"].clone()
+            _, t = timed(lambda: merge_backward(si - 1, dA, dB), few, 2)
+            entry["transition_below_ms"] = float(np.median(t))
+        per_stage.append(entry)
     images = hier["images"]
     flops = sum(algorithmic_flops(st["cfg"]) for st in stages)
     value = images * args.steps / wall_p
     print(json.dumps({
-        "metric": f"reversible backward images/s (PaReprop schedule), {args.workload}-shaped stage stacks",
+        "metric": f"reversible backward images/s (PaReprop schedule), {args.workload}-shaped hierarchy",
         "value": value, "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall_p / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {len(stages)} stages of window-attention shaped reversible stacks, "
-                               f"{images} images of 224x224", "schedule": "pareprop (2 HIP streams)"},
+        "config": {"workload": f"{args.workload}: {len(stages)} stages of window-attention shaped reversible stacks joined by "
+                               f"{len(merges)} stage transitions (stream averaging + patch merging), {images} images of 224x224",
+                   "schedule": "pareprop (2 HIP streams)"},
         "pareprop": {"images_per_s": value, "ms_median": float(np.median(ms_p)), "ms_std": float(ms_p.std())},
         "reprop": {"images_per_s": images * args.steps / wall_r, "ms_median": float(np.median(ms_r)),
                    "ms_std": float(ms_r.std())},
         "pareprop_over_reprop": float(np.median(ms_r)) / float(np.median(ms_p)),
         "algorithmic_tflop_per_step": flops / 1e12,
         "mfma_fraction_whole_path": flops / (float(np.median(ms_p)) * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
+        "finite_gradients": finite,
         "stages": per_stage}))
 
 

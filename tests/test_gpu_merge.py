@@ -100,3 +100,66 @@ def test_merge_rejects_bad_arguments():
         B.rev_merge_forward(c, p, x, x.clone(), workspace=small)
     bad = B.make_merge_cfg(1, 14, 21, 7, 32, "fp32")           # 21 is not a multiple of 2*7
     assert B.rev_merge_check_cfg(bad) < 0
+
+
+def test_two_stage_hierarchy_backward_matches_the_oracle_end_to_end():
+    """Stage 1 stack -> transition -> stage 2 stack, forward then the whole backward (reversible
+    backward of stage 2, backward of the transition fed with its two input cotangents, reversible
+    backward of stage 1), every call through the C-ABI, against the same chain of oracle calls."""
+    from oracle import rev_oracle as O
+    images, w = 2, 2
+    s1 = dict(n_blocks=2, d_model=16, n_heads=2, d_mlp=64, seq_len=w * w, batch=images * 4, mode="fp32")
+    s2 = dict(n_blocks=1, d_model=32, n_heads=4, d_mlp=128, seq_len=w * w, batch=images * 1, mode="fp32")
+    mcfg = dict(batch=images, grid_h=4, grid_w=4, window=w, d_in=16, mode="fp32", ln_eps=1e-5)
+    p1, p2 = synth.make_params(s1, seed=1, perturb=True), synth.make_params(s2, seed=2, perturb=True)
+    pm = synth.make_merge_params(mcfg, seed=3, perturb=True)
+    x, _, _ = synth.make_inputs(s1, seed=1)
+    _, dy1, dy2 = synth.make_inputs(s2, seed=2)
+    print("[case] two-stage hierarchy, fp32", flush=True)
+
+    # ---- oracle
+    b1 = O.unpack_params(p1, s1["n_blocks"], s1["d_model"], s1["d_mlp"])
+    b2 = O.unpack_params(p2, s2["n_blocks"], s2["d_model"], s2["d_mlp"])
+    x64 = x.astype(np.float64)
+    y1, y2 = O.stack_forward(x64, x64, b1, s1["n_heads"], 1e-6)
+    rows = images * 16
+    merged = MO.merge_forward(y1.reshape(rows, -1), y2.reshape(rows, -1), pm, images, 4, 4, w, eps=1e-5)
+    xin2 = merged.reshape(s2["batch"], s2["seq_len"], s2["d_model"])
+    z1, z2 = O.stack_forward(xin2, xin2, b2, s2["n_heads"], 1e-6)
+    r_dx1, r_dx2, r_g2, _, _ = O.stack_backward_reversible(z1, z2, b2, s2["n_heads"], dy1.astype(np.float64),
+                                                          dy2.astype(np.float64), 1e-6)
+    m_dx1, m_dx2, r_gm = MO.merge_backward(y1.reshape(rows, -1), y2.reshape(rows, -1), r_dx1.reshape(rows // 4, -1),
+                                           r_dx2.reshape(rows // 4, -1), pm, images, 4, 4, w, eps=1e-5)
+    f_dx1, f_dx2, r_g1, _, _ = O.stack_backward_reversible(y1, y2, b1, s1["n_heads"], m_dx1.reshape(y1.shape),
+                                                          m_dx2.reshape(y1.shape), 1e-6)
+
+    # ---- HIP path
+    c1, c2, cm = B.make_cfg(**s1), B.make_cfg(**s2), B.make_merge_cfg(**mcfg)
+    P1, P2, PM = to_dev(p1), to_dev(p2), to_dev(pm)
+    X = to_dev(x)
+    Y1, Y2 = B.rev_stack_forward(c1, P1, X, X.clone())
+    merged_g = B.rev_merge_forward(cm, PM, Y1.view(rows, -1), Y2.view(rows, -1))
+    Xin2 = merged_g.view(s2["batch"], s2["seq_len"], s2["d_model"])
+    Z1, Z2 = B.rev_stack_forward(c2, P2, Xin2, Xin2.clone())
+    side = torch.cuda.Stream()
+    res2 = B.rev_stack_backward_pareprop(c2, P2, Z1, Z2, to_dev(dy1), to_dev(dy2), side)
+    resm = B.rev_merge_backward(cm, PM, Y1.view(rows, -1), Y2.view(rows, -1), res2["dX1"].view(rows // 4, -1),
+                                res2["dX2"].view(rows // 4, -1))
+    res1 = B.rev_stack_backward_pareprop(c1, P1, Y1, Y2, resm["dX1"].view(Y1.shape), resm["dX2"].view(Y1.shape), side)
+    torch.cuda.synchronize()
+
+    tol = TOL["fp32"]
+    errs = {"merged": rel_err(merged_g.cpu().numpy(), merged), "dX1": rel_err(res1["dX1"].cpu().numpy(), f_dx1),
+            "dX2": rel_err(res1["dX2"].cpu().numpy(), f_dx2)}
+    gm = MO.unpack_params(resm["dparams"].cpu().numpy(), 16)
+    for k in r_gm:
+        errs["merge.d" + k] = rel_err(gm[k], r_gm[k])
+    for name, res, ref, s in (("s1", res1, r_g1, s1), ("s2", res2, r_g2, s2)):
+        g = O.unpack_params(res["dparams"].cpu().numpy(), s["n_blocks"], s["d_model"], s["d_mlp"])
+        for bi, (gb, rb) in enumerate(zip(g, ref)):
+            for k in rb:
+                errs[f"{name}.blk{bi}.{k}"] = rel_err(gb[k], rb[k])
+    worst = max(errs, key=errs.get)
+    print(f"[ok] worst {worst} {errs[worst]:.2e} over {len(errs)} tensors", flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, bad
