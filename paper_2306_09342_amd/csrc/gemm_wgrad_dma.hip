@@ -32,11 +32,13 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
     const int wp = wave >> 1, wq = wave & 1;                       // 2 x 2 wavefronts, 64 x 64 each
     const int tiles_q = (K + WD_BQ - 1) / WD_BQ;
     const int tiles = ((N + WD_BP - 1) / WD_BP) * tiles_q;
-    const int split = blockIdx.x / tiles;
-    // Each XCD takes one contiguous run of tiles.  The slow tile index is the one along the WIDER
-    // output dimension, so the bigger operand is partitioned over the XCDs' L2s and only the smaller
-    // one is fetched by all of them.
-    const int tile = xcd_remap(blockIdx.x % tiles, tiles);
+    // Each XCD takes one contiguous run of the (token range, tile) order, token range slowest: an XCD
+    // then works on one or two token ranges and on a block of tiles inside them, so both operands are
+    // partitioned over the XCDs' L2s (with every XCD walking all ranges of its tiles, each of them read
+    // the whole of one operand).  The slow tile index is the one along the WIDER output dimension.
+    const int lin = xcd_remap(blockIdx.x, gridDim.x);
+    const int split = lin / tiles;
+    const int tile = lin - split * tiles;
     const int tiles_p = tiles / tiles_q;
     int tp, tq;
     if (K > N) { tq = tile / tiles_p; tp = tile - tq * tiles_p; }
