@@ -513,7 +513,6 @@ static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
                         const Epi& epi) {
     switch (g_nt_variant) {
         case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-        case 3: return launch_dma<160, 128, 1, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
 #ifdef REV_TUNE_VARIANTS
         case 34: return launch_dma<128, 128, 2, 2, 32, 4, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
         case 35: return launch_dma<128, 128, 2, 2, 32, 3, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
@@ -534,10 +533,14 @@ static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
             // 128-row tiles into a single round.  Only for launches that have the device to themselves:
             // next to another stream's kernels that round is filled anyway and the larger LDS footprint
             // keeps the neighbour out (measured: +2.4 % sequential, -5 % parallel schedule).  Never with
-            // fused column sums (their strips are 64 rows).  Each output element sums the same products
+            // fused column sums (their strips are 64 rows), and not for the input-gradient form (weights
+            // read through the LDS transpose read): there the compiler-placed reads of the tall tile lose
+            // to the hand-placed 128x128 loop (63.8 against 60.4 us per launch).  Each output element sums the same products
             // in the same order under either shape, so the choice does not change a bit of the result.
-            if (g_nt_variant != 1 && epi.solo && epi.colsum == nullptr && tall_tiles_pay(M, N))
-                return launch_dma<160, 128, 1, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+            if constexpr (!BKM) {
+                if (g_nt_variant != 1 && epi.solo && epi.colsum == nullptr && tall_tiles_pay(M, N))
+                    return launch_dma<160, 128, 1, 2, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
+            }
             return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
     }
 }

@@ -75,11 +75,11 @@ def test_bf16_mode_matches_oracle(name):
     _run_case(name, "bf16")
 
 
-# Shapes whose GEMMs the sequential schedule and the forward map run with 160-row tiles (128-row tiles
-# would leave a short second round of workgroups) while PaReprop keeps 128-row tiles: oracle parity of
-# the tall-tile kernel with the bias+GELU epilogue (first shape: the wide fc1) and with the residual and
-# plain epilogues, weights read both ways (second shape: every GEMM of a narrow layer over 81 920
-# tokens), and bit-identity of the two schedules across the two tile shapes.
+# Shapes whose forward-form GEMMs the sequential schedule and the forward map run with 160-row tiles
+# (128-row tiles would leave a short second round of workgroups) while PaReprop keeps 128-row tiles:
+# oracle parity of the tall-tile kernel with the bias+GELU epilogue (first shape: the wide fc1) and with
+# the residual epilogue (second shape: proj and fc2 of a narrow layer over 81 920 tokens), and
+# bit-identity of the two schedules across the two tile shapes.
 TALL_SHAPES = {
     "tall_fc1": dict(n_blocks=1, d_model=256, n_heads=4, d_mlp=8192, seq_len=64, batch=20),
     "tall_narrow": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=512, seq_len=64, batch=1280),
