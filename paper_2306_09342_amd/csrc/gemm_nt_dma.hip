@@ -489,8 +489,10 @@ int g_nt_variant = 0;   // tuning hook: tile shape of the pipelined NT GEMM (0 =
 // number of 64-row strips whose column sums the EPI_GELU_BWD epilogue writes (whole tiles, so every
 // strip of every launched workgroup is written, those past M with zeros)
 int gemm_colsum_strips(int M) {
-    const int BM = (g_nt_variant == 2) ? 256 : 128;
-    return ((M + BM - 1) / BM) * (BM / 64);
+#ifdef REV_TUNE_VARIANTS
+    if (g_nt_variant == 2) return ((M + 255) / 256) * 4;
+#endif
+    return ((M + 127) / 128) * 2;
 }
 
 // Cost of a launch in units of "one tile per workgroup slot": the chip holds 512 workgroups of either
@@ -512,8 +514,8 @@ template <int KIND, bool BKM>
 static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                         const Epi& epi) {
     switch (g_nt_variant) {
-        case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
 #ifdef REV_TUNE_VARIANTS
+        case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
         case 34: return launch_dma<128, 128, 2, 2, 32, 4, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
         case 35: return launch_dma<128, 128, 2, 2, 32, 3, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
         case 20: return launch_dma<128, 128, 2, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
