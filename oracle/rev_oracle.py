@@ -20,16 +20,21 @@ What is computed (paper Sec. 3.1, Eq. 1; Sec. 3.2):
 F is the attention branch and G the MLP branch (Sec. 3.2).  The paper does not
 spell out their internals; the readings taken here: pre-LayerNorm inside each
 branch (biased variance, eps a parameter, default 1e-6), multi-head softmax
-attention scaled by head_dim**-0.5 with no mask and no dropout, exact
-(erf-based) GELU, biases on every linear map.
+attention scaled by head_dim**-0.5 with no dropout, exact (erf-based) GELU,
+biases on every linear map.  No mask by default; optionally a key-padding mask
+(one valid length per sample, for the variable-length text batches of the
+Sec. 4.1 language experiments, which the paper does not describe): keys beyond
+a sample's length get probability exactly 0 in every softmax of that sample.
 
 Every function works on float64 arrays shaped [B, T, D] (any leading batch).
 Pins (tests/test_oracle_pins.py): exact inversion, central finite differences,
 reversible == stored-activation gradients, an independent autograd evaluation,
 closed-form LayerNorm / softmax / GELU facts, the T=1 and uniform-attention
 special cases, the zero-output-weights case, token-permutation equivariance,
-batch linearity and the one-F-one-G call count.  No function here is
-"parity unpinned".
+batch linearity and the one-F-one-G call count; the key-padding mask against
+the same computation on the truncated sequences, finite differences under the
+mask and the exactly-zero key/value gradients of masked positions.  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -132,12 +137,22 @@ def _merge_heads(t):              # [B,H,T,dh] -> [B,T,D]
     return t.transpose(0, 2, 1, 3).reshape(B, T, H * dh)
 
 
-def attention(qkv, H):
-    """qkv [B,T,3D], feature order (q|k|v) then head then head_dim."""
+def attention(qkv, H, key_len=None):
+    """qkv [B,T,3D], feature order (q|k|v) then head then head_dim.
+
+    key_len (optional, one integer per sample, 1 <= key_len[b] <= T): key-padding mask -- the keys at
+    positions >= key_len[b] of sample b take no part in any softmax of that sample (score -inf, i.e.
+    probability exactly 0); every query row is still computed.
+    """
     D = qkv.shape[-1] // 3
     q, k, v = (_split_heads(qkv[..., i * D:(i + 1) * D], H) for i in range(3))
     scale = (D // H) ** -0.5
-    P = softmax_rows((q @ k.transpose(0, 1, 3, 2)) * scale)
+    S = (q @ k.transpose(0, 1, 3, 2)) * scale
+    if key_len is not None:
+        S = S.copy()
+        for b, n in enumerate(key_len):
+            S[b, :, :, int(n):] = -np.inf
+    P = softmax_rows(S)
     o = _merge_heads(P @ v)
     return o, (q, k, v, P, scale)
 
@@ -157,11 +172,11 @@ def attention_vjp(do, cache):
 # ----------------------------------------------------------------------------
 # the two branches (Sec. 3.2: F = attention block, G = MLP block)
 # ----------------------------------------------------------------------------
-def F_forward(x, p, H, eps):
+def F_forward(x, p, H, eps, key_len=None):
     CALLS["F"] += 1
     n, ln = layer_norm(x, p["ln1_g"], p["ln1_b"], eps)
     qkv = linear(n, p["w_qkv"], p["b_qkv"])
-    o, att = attention(qkv, H)
+    o, att = attention(qkv, H, key_len)
     return linear(o, p["w_proj"], p["b_proj"]), (n, ln, att, o)
 
 
@@ -196,18 +211,18 @@ def G_vjp(dout, cache, p):
 # ----------------------------------------------------------------------------
 # one reversible block (Eq. 1) and its inverse
 # ----------------------------------------------------------------------------
-def block_forward(x1, x2, p, H, eps, want_cache=False):
-    f, cf = F_forward(x2, p, H, eps)
+def block_forward(x1, x2, p, H, eps, want_cache=False, key_len=None):
+    f, cf = F_forward(x2, p, H, eps, key_len)
     y1 = x1 + f
     g, cg = G_forward(y1, p, eps)
     y2 = x2 + g
     return (y1, y2, (cf, cg)) if want_cache else (y1, y2)
 
 
-def block_inverse(y1, y2, p, H, eps, want_cache=False):
+def block_inverse(y1, y2, p, H, eps, want_cache=False, key_len=None):
     g, cg = G_forward(y1, p, eps)
     x2 = y2 - g
-    f, cf = F_forward(x2, p, H, eps)       # uses the *reconstructed* x2
+    f, cf = F_forward(x2, p, H, eps, key_len)       # uses the *reconstructed* x2
     x1 = y1 - f
     return (x1, x2, (cf, cg)) if want_cache else (x1, x2)
 
@@ -232,23 +247,23 @@ def block_vjp(cache, p, dy1, dy2):
 # ----------------------------------------------------------------------------
 # the stack
 # ----------------------------------------------------------------------------
-def stack_forward(x1, x2, blocks, H, eps=1e-6):
+def stack_forward(x1, x2, blocks, H, eps=1e-6, key_len=None):
     for p in blocks:
-        x1, x2 = block_forward(x1, x2, p, H, eps)
+        x1, x2 = block_forward(x1, x2, p, H, eps, key_len=key_len)
     return x1, x2
 
 
-def stack_inverse(y1, y2, blocks, H, eps=1e-6):
+def stack_inverse(y1, y2, blocks, H, eps=1e-6, key_len=None):
     for p in reversed(blocks):
-        y1, y2 = block_inverse(y1, y2, p, H, eps)
+        y1, y2 = block_inverse(y1, y2, p, H, eps, key_len=key_len)
     return y1, y2
 
 
-def stack_backward_stored(x1, x2, blocks, H, dy1, dy2, eps=1e-6):
+def stack_backward_stored(x1, x2, blocks, H, dy1, dy2, eps=1e-6, key_len=None):
     """Ordinary backprop: forward keeps every block's intermediates, then reverse mode."""
     caches = []
     for p in blocks:
-        x1, x2, c = block_forward(x1, x2, p, H, eps, want_cache=True)
+        x1, x2, c = block_forward(x1, x2, p, H, eps, want_cache=True, key_len=key_len)
         caches.append(c)
     grads = [None] * len(blocks)
     for i in reversed(range(len(blocks))):
@@ -256,7 +271,7 @@ def stack_backward_stored(x1, x2, blocks, H, dy1, dy2, eps=1e-6):
     return dy1, dy2, grads
 
 
-def stack_backward_reversible(y1, y2, blocks, H, dy1, dy2, eps=1e-6):
+def stack_backward_reversible(y1, y2, blocks, H, dy1, dy2, eps=1e-6, key_len=None):
     """Sec. 3.2 (Reprop): top block first -- invert, backpropagate, drop, repeat.
 
     Returns (dX1, dX2, per-block grads, X1, X2) where X1, X2 are the
@@ -265,7 +280,7 @@ def stack_backward_reversible(y1, y2, blocks, H, dy1, dy2, eps=1e-6):
     """
     grads = [None] * len(blocks)
     for i in reversed(range(len(blocks))):
-        x1, x2, cache = block_inverse(y1, y2, blocks[i], H, eps, want_cache=True)
+        x1, x2, cache = block_inverse(y1, y2, blocks[i], H, eps, want_cache=True, key_len=key_len)
         dy1, dy2, grads[i] = block_vjp(cache, blocks[i], dy1, dy2)
         y1, y2 = x1, x2
     return dy1, dy2, grads, y1, y2
@@ -281,7 +296,7 @@ def add_grads(acc, grads):
     return acc
 
 
-def stack_backward_reversible_chunked(y1, y2, blocks, H, dy1, dy2, eps=1e-6, chunk=8):
+def stack_backward_reversible_chunked(y1, y2, blocks, H, dy1, dy2, eps=1e-6, chunk=8, key_len=None):
     """Same result as stack_backward_reversible, walking the batch in chunks to bound memory."""
     B = y1.shape[0]
     dx1 = np.empty_like(y1, dtype=F64)
@@ -293,7 +308,8 @@ def stack_backward_reversible_chunked(y1, y2, blocks, H, dy1, dy2, eps=1e-6, chu
         sl = slice(s, min(B, s + chunk))
         a, b, g, c, d = stack_backward_reversible(
             np.asarray(y1[sl], F64), np.asarray(y2[sl], F64), blocks, H,
-            np.asarray(dy1[sl], F64), np.asarray(dy2[sl], F64), eps)
+            np.asarray(dy1[sl], F64), np.asarray(dy2[sl], F64), eps,
+            key_len=None if key_len is None else key_len[sl])
         dx1[sl], dx2[sl], x1[sl], x2[sl] = a, b, c, d
         acc = add_grads(acc, g)
     return dx1, dx2, acc, x1, x2

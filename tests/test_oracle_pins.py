@@ -364,3 +364,101 @@ def test_synth_recipe():
     assert np.all(r.view(np.uint32) & 0xFFFF == 0)
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0078125     # tie -> even, then up
     assert np.array_equal(r, torch.tensor(v).to(torch.bfloat16).float().numpy())
+
+
+# ---------------------------------------------------------------- key-padding mask
+KEY_LEN = np.array([16, 9, 1, 12])          # tiny config: 4 samples of 16 tokens
+
+
+def test_masked_attention_equals_attention_on_the_truncated_sequence():
+    """Valid query rows see exactly what they would see if the padded keys did not exist; padded query
+    rows are a softmax over the valid keys only (brute-force loop); masked probabilities are exactly 0.
+    Catches masking the wrong axis (queries instead of keys), an off-by-one in the length and a finite
+    'large negative' stand-in that leaks probability."""
+    rng = np.random.default_rng(0)
+    B, T, H, dh = 4, 16, 2, 8
+    D = H * dh
+    qkv = rng.standard_normal((B, T, 3 * D))
+    o, (q, k, v, P, scale) = O.attention(qkv, H, KEY_LEN)
+    for b, n in enumerate(KEY_LEN):
+        assert np.all(P[b, :, :, n:] == 0.0)
+        assert np.allclose(P[b].sum(axis=-1), 1.0, atol=1e-14)
+        o_trunc, _ = O.attention(qkv[b:b + 1, :n], H)
+        assert np.abs(o[b, :n] - o_trunc[0]).max() < 1e-13
+        # a padded query row, by hand
+        i = T - 1
+        for h in range(H):
+            s = np.array([q[b, h, i] @ k[b, h, j] for j in range(n)]) * scale
+            w = np.exp(s - s.max())
+            w /= w.sum()
+            want = sum(w[j] * v[b, h, j] for j in range(n))
+            assert np.abs(o[b, i, h * dh:(h + 1) * dh] - want).max() < 1e-13
+
+
+def test_masked_keys_and_values_get_exactly_zero_gradient():
+    rng = np.random.default_rng(1)
+    B, T, H, dh = 4, 16, 2, 8
+    D = H * dh
+    qkv = rng.standard_normal((B, T, 3 * D))
+    do = rng.standard_normal((B, T, D))
+    _, cache = O.attention(qkv, H, KEY_LEN)
+    dqkv = O.attention_vjp(do, cache)
+    for b, n in enumerate(KEY_LEN):
+        assert np.all(dqkv[b, n:, D:] == 0.0)            # dK and dV of padded positions
+        if 1 < n < T:                                    # (one valid key: the softmax is constant, dQ = 0)
+            assert np.abs(dqkv[b, n:, :D]).max() > 0     # padded queries still have a dQ
+
+
+def test_masked_stack_equals_the_stack_on_truncated_sequences():
+    """With cotangents that vanish on the padded positions, every valid-position output and every
+    parameter gradient equals the computation on the truncated sequences, sample by sample."""
+    cfg, blocks, x, dy1, dy2 = _setup()
+    H = cfg["n_heads"]
+    for b, n in enumerate(KEY_LEN):
+        dy1[b, n:] = 0.0
+        dy2[b, n:] = 0.0
+    y1, y2 = O.stack_forward(x, x, blocks, H, EPS, key_len=KEY_LEN)
+    dx1, dx2, grads, rx1, rx2 = O.stack_backward_reversible(y1, y2, blocks, H, dy1, dy2, EPS, key_len=KEY_LEN)
+    assert np.abs(rx1 - x).max() < 1e-12 and np.abs(rx2 - x).max() < 1e-12      # inversion holds under the mask
+    acc = None
+    for b, n in enumerate(KEY_LEN):
+        xs = x[b:b + 1, :n]
+        t1, t2 = O.stack_forward(xs, xs, blocks, H, EPS)
+        assert np.abs(t1[0] - y1[b, :n]).max() < 1e-12 and np.abs(t2[0] - y2[b, :n]).max() < 1e-12
+        a1, a2, g, _, _ = O.stack_backward_reversible(t1, t2, blocks, H, dy1[b:b + 1, :n], dy2[b:b + 1, :n], EPS)
+        assert _rel(dx1[b, :n], a1[0]) < 1e-10 and _rel(dx2[b, :n], a2[0]) < 1e-10
+        assert np.all(dx1[b, n:] == 0.0) and np.all(dx2[b, n:] == 0.0)
+        acc = O.add_grads(acc, g)
+    for gb, ab in zip(grads, acc):
+        for name in gb:
+            assert _rel(gb[name], ab[name]) < 1e-9, name
+
+
+def test_masked_backward_matches_finite_differences_and_the_stored_route():
+    cfg, blocks, x, dy1, dy2 = _setup()
+    H = cfg["n_heads"]
+    x2 = x[::-1].copy()
+    y1, y2 = O.stack_forward(x, x2, blocks, H, EPS, key_len=KEY_LEN)
+    dx1, dx2, grads, _, _ = O.stack_backward_reversible(y1, y2, blocks, H, dy1, dy2, EPS, key_len=KEY_LEN)
+    s1, s2, sg = O.stack_backward_stored(x, x2, blocks, H, dy1, dy2, EPS, key_len=KEY_LEN)
+    assert _rel(dx1, s1) < 1e-10 and _rel(dx2, s2) < 1e-10
+
+    def loss(a1, a2, bl):
+        o1, o2 = O.stack_forward(a1, a2, bl, H, EPS, key_len=KEY_LEN)
+        return float(np.sum(o1 * dy1) + np.sum(o2 * dy2))
+
+    rng = np.random.default_rng(2)
+    h = 1e-6
+    for trial in range(3):
+        d = rng.standard_normal(x.shape)
+        fd = (loss(x, x2 + h * d, blocks) - loss(x, x2 - h * d, blocks)) / (2 * h)
+        assert abs(fd - float(np.sum(dx2 * d))) <= 1e-6 * max(1.0, abs(fd))
+    for name in ("w_qkv", "b_qkv", "w_proj", "ln1_g"):
+        d = rng.standard_normal(blocks[1][name].shape)
+        plus = [dict(p) for p in blocks]
+        minus = [dict(p) for p in blocks]
+        plus[1][name] = blocks[1][name] + h * d
+        minus[1][name] = blocks[1][name] - h * d
+        fd = (loss(x, x2, plus) - loss(x, x2, minus)) / (2 * h)
+        an = float(np.sum(grads[1][name] * d))
+        assert abs(fd - an) <= 1e-6 * max(1.0, abs(an)), name
