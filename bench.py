@@ -496,6 +496,27 @@ def main():
         "finite_after_steps": bool(torch.isfinite(master).all().item()),
     }
 
+    # ---- padded text batches (text workloads only): the same backward pass with a key-padding mask,
+    # lengths drawn once from a seeded uniform law on [T/8, T] as a stand-in for variable-length text
+    if args.workload.startswith("roberta"):
+        lens = synth.make_key_lengths(cfg, seed=0)
+        klen = torch.from_numpy(lens).cuda()
+        Ym1, Ym2 = B.rev_stack_forward_masked(c, params, X, X, klen, workspace=ws)
+        B.rev_stack_backward_reprop_masked(c, params, Ym1, Ym2, klen, dY1, dY2, workspace=ws, out=out)
+        torch.cuda.synchronize()
+        few = max(5, args.steps // 2)
+        _, ms_mp = timed(lambda: B.rev_stack_backward_pareprop_masked(c, params, Ym1, Ym2, klen, dY1, dY2, side,
+                                                                      workspace=ws, out=out), few, 3)
+        _, ms_mr = timed(lambda: B.rev_stack_backward_reprop_masked(c, params, Ym1, Ym2, klen, dY1, dY2,
+                                                                    workspace=ws, out=out), few, 3)
+        line["key_padding_mask"] = {
+            "what": "same pass through the *_masked entry points, key lengths ~ U[T/8, T] (seed 0)",
+            "mean_length": float(lens.mean()), "min_length": int(lens.min()),
+            "pareprop": {"samples_per_s": Bsz / (float(np.median(ms_mp)) * 1e-3), "ms_median": float(np.median(ms_mp))},
+            "reprop": {"samples_per_s": Bsz / (float(np.median(ms_mr)) * 1e-3), "ms_median": float(np.median(ms_mr))},
+            "finite": bool(torch.isfinite(out["dparams"]).all().item()),
+        }
+
     if not args.no_cpu_baseline:
         from oracle import rev_oracle as O
         blocks = O.unpack_params(flat, cfg["n_blocks"], cfg["d_model"], cfg["d_mlp"])

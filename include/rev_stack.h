@@ -184,6 +184,37 @@ int rev_adamw_step(int64_t n, float* master, void* params_bf16, const float* gra
                    float* m, float* v, int32_t step, float lr, float beta1, float beta2,
                    float eps, float weight_decay, void* stream);
 
+/* The same three calls with a key-padding mask, for batches of sequences of
+ * different lengths padded to seq_len (the variable-length text batches of the
+ * paper's language experiments, Sec. 4.1; the paper does not describe the mask,
+ * this is the common one).  key_len: device pointer to `batch` int32 values;
+ * in every attention of sample b the keys at positions >= key_len[b] get
+ * probability exactly 0.  Values are clamped to [1, seq_len] (a softmax needs
+ * one key).  All seq_len query rows of every sample are still computed and
+ * returned, padded positions included: they flow through the blocks like any
+ * token but no valid position ever reads them, so with cotangents that vanish
+ * on the padded positions every result at a valid position and every parameter
+ * gradient equals that of the unpadded sequences.  Everything else (arguments,
+ * workspace sizes, ordering, errors, bit-identity of the two schedules) is as
+ * for the unmasked calls; key_len must not be null here. */
+int rev_stack_forward_masked(const rev_cfg* cfg, const void* params,
+                             const float* X1, const float* X2, const int32_t* key_len,
+                             float* Y1, float* Y2,
+                             void* workspace, int64_t workspace_bytes, void* stream);
+int rev_stack_backward_reprop_masked(const rev_cfg* cfg, const void* params,
+                                     const float* Y1, const float* Y2, const int32_t* key_len,
+                                     const float* dY1, const float* dY2,
+                                     float* dX1, float* dX2,
+                                     float* X1_out, float* X2_out, float* dparams,
+                                     void* workspace, int64_t workspace_bytes, void* stream);
+int rev_stack_backward_pareprop_masked(const rev_cfg* cfg, const void* params,
+                                       const float* Y1, const float* Y2, const int32_t* key_len,
+                                       const float* dY1, const float* dY2,
+                                       float* dX1, float* dX2,
+                                       float* X1_out, float* X2_out, float* dparams,
+                                       void* workspace, int64_t workspace_bytes,
+                                       void* stream_grad, void* stream_recompute);
+
 /* Measurement aid for the hidden-recompute fraction: runs only one of the two
  * chains of the backward pass on `stream`.  chain = 0: the recomputation chain
  * R_N..R_1 alone (writes X1_out/X2_out if given).  chain = 1: the gradient

@@ -23,6 +23,7 @@ EXPORTS = (
     "rev_stack_check_cfg", "rev_stack_param_count", "rev_stack_param_offset", "rev_stack_workspace_bytes",
     "rev_stack_workspace_bytes_reprop", "rev_stack_slot_bytes",
     "rev_stack_forward", "rev_stack_backward_reprop", "rev_stack_backward_pareprop", "rev_stack_backward_chain",
+    "rev_stack_forward_masked", "rev_stack_backward_reprop_masked", "rev_stack_backward_pareprop_masked",
     "rev_adamw_step",
     "rev_merge_check_cfg", "rev_merge_param_count", "rev_merge_workspace_bytes", "rev_merge_forward", "rev_merge_backward",
     "rev_profile_begin", "rev_profile_end", "rev_profile_kinds", "rev_profile_name", "rev_profile_is_flops",
@@ -76,6 +77,13 @@ def lib():
         L.rev_stack_backward_pareprop.restype = ctypes.c_int
         L.rev_stack_backward_chain.argtypes = bw + [vp, i32]
         L.rev_stack_backward_chain.restype = ctypes.c_int
+        L.rev_stack_forward_masked.argtypes = [cp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+        L.rev_stack_forward_masked.restype = ctypes.c_int
+        bwm = [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64]
+        L.rev_stack_backward_reprop_masked.argtypes = bwm + [vp]
+        L.rev_stack_backward_reprop_masked.restype = ctypes.c_int
+        L.rev_stack_backward_pareprop_masked.argtypes = bwm + [vp, vp]
+        L.rev_stack_backward_pareprop_masked.restype = ctypes.c_int
         f32 = ctypes.c_float
         L.rev_adamw_step.argtypes = [i64, vp, vp, vp, vp, vp, i32, f32, f32, f32, f32, f32, vp]
         L.rev_adamw_step.restype = ctypes.c_int
@@ -220,6 +228,46 @@ def rev_stack_backward_pareprop(cfg, params, Y1, Y2, dY1, dY2, stream_recompute,
                                 want_inputs=False, out=None):
     args, res = _backward_args(cfg, params, Y1, Y2, dY1, dY2, workspace, want_inputs, out)
     _check(lib().rev_stack_backward_pareprop(*args, _stream_handle(stream_grad), _stream_handle(stream_recompute)))
+    return res
+
+
+def _want_key_len(cfg, key_len):
+    _want(key_len, torch.int32, (cfg.batch,))
+
+
+def rev_stack_forward_masked(cfg, params, X1, X2, key_len, workspace=None, stream=None, Y1=None, Y2=None):
+    """rev_stack_forward with a key-padding mask: key_len is an int32 CUDA tensor [batch] of valid lengths."""
+    shape = (cfg.batch, cfg.seq_len, cfg.d_model)
+    _want(params, param_dtype(cfg), (rev_stack_param_count(cfg),))
+    _want(X1, torch.float32, shape)
+    _want(X2, torch.float32, shape)
+    _want_key_len(cfg, key_len)
+    Y1 = torch.empty_like(X1) if Y1 is None else Y1
+    Y2 = torch.empty_like(X2) if Y2 is None else Y2
+    ws = alloc_workspace(cfg, X1.device) if workspace is None else workspace
+    _check(lib().rev_stack_forward_masked(ctypes.byref(cfg), _ptr(params), _ptr(X1), _ptr(X2), _ptr(key_len), _ptr(Y1),
+                                          _ptr(Y2), _ptr(ws), ws.numel(), _stream_handle(stream)))
+    return Y1, Y2
+
+
+def _masked(args, key_len):
+    return args[:4] + [_ptr(key_len)] + args[4:]
+
+
+def rev_stack_backward_reprop_masked(cfg, params, Y1, Y2, key_len, dY1, dY2, workspace=None, stream=None,
+                                     want_inputs=False, out=None):
+    _want_key_len(cfg, key_len)
+    args, res = _backward_args(cfg, params, Y1, Y2, dY1, dY2, workspace, want_inputs, out)
+    _check(lib().rev_stack_backward_reprop_masked(*_masked(args, key_len), _stream_handle(stream)))
+    return res
+
+
+def rev_stack_backward_pareprop_masked(cfg, params, Y1, Y2, key_len, dY1, dY2, stream_recompute, workspace=None,
+                                       stream_grad=None, want_inputs=False, out=None):
+    _want_key_len(cfg, key_len)
+    args, res = _backward_args(cfg, params, Y1, Y2, dY1, dY2, workspace, want_inputs, out)
+    _check(lib().rev_stack_backward_pareprop_masked(*_masked(args, key_len), _stream_handle(stream_grad),
+                                                    _stream_handle(stream_recompute)))
     return res
 
 

@@ -111,7 +111,8 @@ __device__ __forceinline__ void store4_bf16(bf16* p, float a, float b, float c, 
 // ----------------------------------------------------------------------------------------
 template <int DHP, bool PIPE>
 __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qkv, bf16* __restrict__ o,
-                                                     float* __restrict__ lse, int T, int H, int dh, int trows) {
+                                                     float* __restrict__ lse, const int* __restrict__ key_len,
+                                                     int T, int H, int dh, int trows) {
     // trows: streamed rows held in LDS at a time -- 64, or all ceil32(T) rows when they fit (one load, no
     // further barriers)
     using C = AtCfg<DHP>;
@@ -127,6 +128,8 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
     const int q0 = (blockIdx.x * nw + wave) * 32;
     // scores are kept in the base-2 domain (scale * log2 e folded into one multiply, exp2 is one instruction)
     const float c2 = rsqrtf((float)dh) * 1.4426950408889634f;
+    // key-padding mask: keys at positions >= Tk take no part in the softmax (Tk = T without a mask)
+    const int Tk = key_len ? min(max(key_len[b], 1), T) : T;
 
     bf16x8_t bq[C::KS];
     load_owned<DHP>(base, ld, q0, T, dh, lane, bq);
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
         tile_fetch<DHP>(pk, base + D, ld, 0, T, dh);
         tile_fetch<DHP>(pv, base + 2 * D, ld, 0, T, dh);
     }
-    for (int t0 = 0; t0 < T; t0 += trows) {
+    for (int t0 = 0; t0 < Tk; t0 += trows) {
       __syncthreads();
       if constexpr (pipe) {
           tile_store<DHP>(Ks0, pk);
@@ -155,14 +158,14 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
           load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
       }
       __syncthreads();
-      if (pipe) if (t0 + trows < T) {
+      if (pipe) if (t0 + trows < Tk) {
           tile_fetch<DHP>(pk, base + D, ld, t0 + trows, T, dh);
           tile_fetch<DHP>(pv, base + 2 * D, ld, t0 + trows, T, dh);
       }
-      for (int k0 = t0; k0 < min(T, t0 + trows); k0 += AT_ROWS) {
+      for (int k0 = t0; k0 < min(Tk, t0 + trows); k0 += AT_ROWS) {
         const uint16_t* Ks = Ks0 + (k0 - t0) * C::PITCH;
         const uint16_t* Vs = Vs0 + (k0 - t0) * C::PITCH;
-        const int nt = (T - k0 > 32) ? 2 : 1;
+        const int nt = (Tk - k0 > 32) ? 2 : 1;
         float s[2][16];
         float mloc = -INFINITY;
 #pragma unroll
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
 #pragma unroll
                 for (int ks = 0; ks < C::KS; ++ks)
                     acc = mfma32(*reinterpret_cast<const bf16x8_t*>(kp + 16 * ks), bq[ks], acc);
-                if (k0 + t * 32 + 32 <= T) {               // whole tile inside the sequence: no masking
+                if (k0 + t * 32 + 32 <= Tk) {               // whole tile inside the sequence: no masking
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         s[t][v] = acc[v] * c2;
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(512) void attn_fwd_mfma(const bf16* __restrict__ qk
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                        s[t][v] = (key < T) ? acc[v] * c2 : -INFINITY;
+                        s[t][v] = (key < Tk) ? acc[v] * c2 : -INFINITY;
                         mloc = fmaxf(mloc, s[t][v]);
                     }
                 }
@@ -251,7 +254,7 @@ template <int DHP, bool PIPE>
 __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                         const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                         bf16* __restrict__ dqkv, float* __restrict__ delta,
-                                                        int T, int H, int dh, int trows) {
+                                                        const int* __restrict__ key_len, int T, int H, int dh, int trows) {
     using C = AtCfg<DHP>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t* Ks0 = reinterpret_cast<uint16_t*>(smem);
@@ -268,6 +271,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
     const int q = q0 + (lane & 31), qc = min(q, T - 1);
     const float scale = rsqrtf((float)dh);
     const float c2 = scale * 1.4426950408889634f;
+    // key-padding mask: keys at positions >= Tk take no part in the softmax (Tk = T without a mask)
+    const int Tk = key_len ? min(max(key_len[b], 1), T) : T;
 
     bf16x8_t bq[C::KS], bdo[C::KS];
     load_owned<DHP>(base, ld, q0, T, dh, lane, bq);
@@ -298,7 +303,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
         tile_fetch<DHP>(pk, base + D, ld, 0, T, dh);
         tile_fetch<DHP>(pv, base + 2 * D, ld, 0, T, dh);
     }
-    for (int t0 = 0; t0 < T; t0 += trows) {
+    for (int t0 = 0; t0 < Tk; t0 += trows) {
       __syncthreads();
       if constexpr (pipe) {
           tile_store<DHP>(Ks0, pk);
@@ -308,14 +313,14 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
           load_tile<DHP>(Vs0, base + 2 * D, ld, t0, T, dh, trows);
       }
       __syncthreads();
-      if (pipe) if (t0 + trows < T) {
+      if (pipe) if (t0 + trows < Tk) {
           tile_fetch<DHP>(pk, base + D, ld, t0 + trows, T, dh);
           tile_fetch<DHP>(pv, base + 2 * D, ld, t0 + trows, T, dh);
       }
-      for (int k0 = t0; k0 < min(T, t0 + trows); k0 += AT_ROWS) {
+      for (int k0 = t0; k0 < min(Tk, t0 + trows); k0 += AT_ROWS) {
         const uint16_t* Ks = Ks0 + (k0 - t0) * C::PITCH;
         const uint16_t* Vs = Vs0 + (k0 - t0) * C::PITCH;
-        const int nt = (T - k0 > 32) ? 2 : 1;
+        const int nt = (Tk - k0 > 32) ? 2 : 1;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             if (t < nt) {
@@ -331,7 +336,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
                 }
                 // dS without its 1/sqrt(head_dim): that factor is applied once to the finished dQ
                 float ds[16];
-                if (k0 + t * 32 + 32 <= T) {
+                if (k0 + t * 32 + 32 <= Tk) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
                         ds[v] = __builtin_amdgcn_exp2f(aS[v] * c2 - L2) * (aP[v] - dl);
@@ -339,7 +344,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int key = k0 + t * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                        ds[v] = (key < T) ? __builtin_amdgcn_exp2f(aS[v] * c2 - L2) * (aP[v] - dl) : 0.f;
+                        ds[v] = (key < Tk) ? __builtin_amdgcn_exp2f(aS[v] * c2 - L2) * (aP[v] - dl) : 0.f;
                     }
                 }
 #pragma unroll
@@ -375,7 +380,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_mfma(const bf16* __restrict__
 template <int DHP, bool PIPE>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16* __restrict__ dqkv, int T, int H, int dh, int trows) {
+                                                         bf16* __restrict__ dqkv, const int* __restrict__ key_len,
+                                                         int T, int H, int dh, int trows) {
     using C = AtCfg<DHP>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t* Qs0 = reinterpret_cast<uint16_t*>(smem);
@@ -392,6 +398,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
     const int j0 = (blockIdx.x * nw + wave) * 32;
     const float scale = rsqrtf((float)dh);
     const float c2 = scale * 1.4426950408889634f;
+    const int Tk = key_len ? min(max(key_len[b], 1), T) : T;      // keys beyond Tk are masked: their dK, dV are zero
 
     bf16x8_t bk[C::KS], bv[C::KS];
     load_owned<DHP>(base + D, ld, j0, T, dh, lane, bk);
@@ -492,6 +499,12 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
       }
     }
     const int j = j0 + (lane & 31);
+    if (j >= Tk) {                       // a masked key: no query looked at it
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { accK[dt][v] = 0.f; accV[dt][v] = 0.f; }
+    }
     if (j < T) {
         bf16* dk = dqkv + ((int64_t)b * T + j) * ld + D + h * dh;
         bf16* dv = dk + D;
@@ -541,7 +554,7 @@ static int raise_lds(K kern, size_t shmem) {
 }
 
 template <int DHP>
-static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B, int T, int H, int dh) {
+static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B, int T, int H, int dh, const int* key_len) {
     int nblk, nw;
     row_split(T, &nblk, &nw);
     const int trows = tile_rows<DHP>(T);
@@ -549,14 +562,14 @@ static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B
     // (the register prefetch of the streamed mode costs the forward kernel one resident wavefront per
     // SIMD and measured slower there; the backward kernels gain 20 % from it)
     RC_LDS(raise_lds(attn_fwd_mfma<DHP, false>, shmem));
-    hipLaunchKernelGGL((attn_fwd_mfma<DHP, false>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, lse, T, H, dh, trows);
+    hipLaunchKernelGGL((attn_fwd_mfma<DHP, false>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, lse, key_len, T, H, dh, trows);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
 
 template <int DHP>
 static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse, bf16* dqkv,
-                      float* delta, int B, int T, int H, int dh) {
+                      float* delta, int B, int T, int H, int dh, const int* key_len) {
     int nblk, nw;
     row_split(T, &nblk, &nw);
     // With 4 or more wavefronts the backward kernels always stream 64-row tiles with the next tile
@@ -567,16 +580,16 @@ static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16*
     const size_t shmem2 = shmem + 2 * trows * sizeof(float);
     if (trows == AT_ROWS && nw >= 4) {          // streamed mode with register prefetch of the next tile
         hipLaunchKernelGGL((attn_bwd_dq_mfma<DHP, true>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, dout, lse, dqkv,
-                           delta, T, H, dh, trows);
+                           delta, key_len, T, H, dh, trows);
         hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP, true>), dim3(nblk, B * H), dim3(nw * 64), shmem2, s, qkv, dout, lse, delta,
-                           dqkv, T, H, dh, trows);
+                           dqkv, key_len, T, H, dh, trows);
     } else {
         RC_LDS(raise_lds(attn_bwd_dq_mfma<DHP, false>, shmem));
         RC_LDS(raise_lds(attn_bwd_dkv_mfma<DHP, false>, shmem2));
         hipLaunchKernelGGL((attn_bwd_dq_mfma<DHP, false>), dim3(nblk, B * H), dim3(nw * 64), shmem, s, qkv, o, dout, lse, dqkv,
-                           delta, T, H, dh, trows);
+                           delta, key_len, T, H, dh, trows);
         hipLaunchKernelGGL((attn_bwd_dkv_mfma<DHP, false>), dim3(nblk, B * H), dim3(nw * 64), shmem2, s, qkv, dout, lse, delta,
-                           dqkv, T, H, dh, trows);
+                           dqkv, key_len, T, H, dh, trows);
     }
     REV_HIP(hipGetLastError());
     return REV_OK;
@@ -587,35 +600,35 @@ static bool mfma_ok(const void* a, const void* b, const void* c, const void* d) 
 }
 
 template <>
-int attention_forward<bf16>(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B, int T, int H, int dh) {
+int attention_forward<bf16>(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B, int T, int H, int dh, const int* key_len) {
     if ((dh & 7) || dh > 128 || !mfma_ok(qkv, o, nullptr, nullptr))
-        return attention_forward_simple<bf16>(s, qkv, o, lse, B, T, H, dh);
+        return attention_forward_simple<bf16>(s, qkv, o, lse, B, T, H, dh, key_len);
     ProfScope ps(K_ATTN_FWD, s, 4.0 * B * H * (double)T * T * dh);
-    if (dh <= 32) return fwd_launch<32>(s, qkv, o, lse, B, T, H, dh);
-    if (dh <= 64) return fwd_launch<64>(s, qkv, o, lse, B, T, H, dh);
-    if (dh <= 96) return fwd_launch<96>(s, qkv, o, lse, B, T, H, dh);
-    return fwd_launch<128>(s, qkv, o, lse, B, T, H, dh);
+    if (dh <= 32) return fwd_launch<32>(s, qkv, o, lse, B, T, H, dh, key_len);
+    if (dh <= 64) return fwd_launch<64>(s, qkv, o, lse, B, T, H, dh, key_len);
+    if (dh <= 96) return fwd_launch<96>(s, qkv, o, lse, B, T, H, dh, key_len);
+    return fwd_launch<128>(s, qkv, o, lse, B, T, H, dh, key_len);
 }
 template <>
-int attention_forward<float>(hipStream_t s, const float* qkv, float* o, float* lse, int B, int T, int H, int dh) {
-    return attention_forward_simple<float>(s, qkv, o, lse, B, T, H, dh);
+int attention_forward<float>(hipStream_t s, const float* qkv, float* o, float* lse, int B, int T, int H, int dh, const int* key_len) {
+    return attention_forward_simple<float>(s, qkv, o, lse, B, T, H, dh, key_len);
 }
 
 template <>
 int attention_backward<bf16>(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse,
-                             bf16* dqkv, float* delta, int B, int T, int H, int dh) {
+                             bf16* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len) {
     if ((dh & 7) || dh > 128 || !mfma_ok(qkv, o, dout, dqkv))
-        return attention_backward_simple<bf16>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+        return attention_backward_simple<bf16>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
     ProfScope ps(K_ATTN_BWD, s, 8.0 * B * H * (double)T * T * dh);
-    if (dh <= 32) return bwd_launch<32>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
-    if (dh <= 64) return bwd_launch<64>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
-    if (dh <= 96) return bwd_launch<96>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
-    return bwd_launch<128>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+    if (dh <= 32) return bwd_launch<32>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
+    if (dh <= 64) return bwd_launch<64>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
+    if (dh <= 96) return bwd_launch<96>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
+    return bwd_launch<128>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
 }
 template <>
 int attention_backward<float>(hipStream_t s, const float* qkv, const float* o, const float* dout, const float* lse,
-                              float* dqkv, float* delta, int B, int T, int H, int dh) {
-    return attention_backward_simple<float>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh);
+                              float* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len) {
+    return attention_backward_simple<float>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
 }
 
 }  // namespace rev

@@ -161,10 +161,11 @@ int gemm_nt_bf16_simple(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
 int gemm_wgrad_bf16_simple(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
                            int M, int N, int K, float* dW);
 template <typename T>
-int attention_forward_simple(hipStream_t s, const T* qkv, T* o, float* lse, int B, int T_, int H, int dh);
+int attention_forward_simple(hipStream_t s, const T* qkv, T* o, float* lse, int B, int T_, int H, int dh,
+                             const int* key_len = nullptr);
 template <typename T>
 int attention_backward_simple(hipStream_t s, const T* qkv, const T* o, const T* dout, const float* lse,
-                              T* dqkv, float* delta, int B, int T_, int H, int dh);
+                              T* dqkv, float* delta, int B, int T_, int H, int dh, const int* key_len = nullptr);
 
 // ---- memory-bound kernels ---------------------------------------------------------
 // y = LN(x; g, b), stats[2*row] = mean, stats[2*row+1] = rstd
@@ -189,11 +190,14 @@ int64_t colsum_partial_elems(int M, int N);
 int convert_f32_to_bf16(hipStream_t s, const float* in, bf16* out, int64_t n);
 
 // ---- attention ----------------------------------------------------------------------
-// qkv [B*T, 3D] (q|k|v, head-major inside each), o [B*T, D], lse [B, H, T]
+// qkv [B*T, 3D] (q|k|v, head-major inside each), o [B*T, D], lse [B, H, T].
+// key_len (nullable, device, [B]): key-padding mask -- the keys at positions >= key_len[b] (clamped to
+// [1, T]) of sample b are left out of every softmax of that sample; all T query rows are computed.
 template <typename TA>
-int attention_forward(hipStream_t s, const TA* qkv, TA* o, float* lse, int B, int T, int H, int dh);
+int attention_forward(hipStream_t s, const TA* qkv, TA* o, float* lse, int B, int T, int H, int dh,
+                      const int* key_len = nullptr);
 template <typename TA>
 int attention_backward(hipStream_t s, const TA* qkv, const TA* o, const TA* dout, const float* lse,
-                       TA* dqkv, float* delta, int B, int T, int H, int dh);
+                       TA* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len = nullptr);
 
 }  // namespace rev

@@ -233,6 +233,7 @@ struct Runner {
     float* dparams;
     int M, D, Dm, H, dh, B, Tn;
     bool solo;      // one stream: every kernel has the device to itself
+    const int* key_len = nullptr;   // optional key-padding mask: valid keys per sample (device, [batch])
 
     Runner(const rev_cfg& cfg, const void* p, float* dp, void* w, bool compact)
         : c(cfg), L(make_layout(cfg, compact)), ws((char*)w), params((const T*)p), dparams(dp), solo(compact) {
@@ -254,7 +255,7 @@ struct Runner {
         RC((ln_forward<T, T>(s, x2, P(blk, T_LN1G), P(blk, T_LN1B), c.ln_eps, sl.n1, sl.st1, M, D)));
         Epi e = epi0(); e.kind = EPI_BIAS; e.out = sl.qkv; e.bias = P(blk, T_BQKV); e.ldo = 3 * D;
         RC(Ops<T>::nt(s, sl.n1, D, P(blk, T_WQKV), D, M, 3 * D, D, e));
-        RC((attention_forward<T>(s, sl.qkv, sl.o, sl.lse, B, Tn, H, dh)));
+        RC((attention_forward<T>(s, sl.qkv, sl.o, sl.lse, B, Tn, H, dh, key_len)));
         return REV_OK;
     }
     // out1 = in1 + sign * (o Wp^T + bp)
@@ -340,7 +341,7 @@ struct Runner {
         // ---- F branch
         Epi q = epi0(); q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
         RC(dgrad(s, blk, T_WPROJ, gy1b, D, D, q));
-        RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh)));
+        RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh, key_len)));
         if (ev) REV_HIP(hipEventRecord(ev[2], s));
         Epi r = epi0(); r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
         RC(dgrad(s, blk, T_WQKV, dqkv, 3 * D, D, r));
@@ -512,7 +513,8 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 static int backward_entry(int schedule, const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
                           const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1o, float* X2o,
-                          float* dparams, void* ws, int64_t ws_bytes, void* sv, void* sr) {
+                          float* dparams, void* ws, int64_t ws_bytes, void* sv, void* sr,
+                          const int32_t* key_len = nullptr) {
     const bool compact = schedule == 0;          // the sequential schedule runs in the smaller layout
     RC(check_common(cfg, ws, ws_bytes, compact));
     if (!params || !Y1 || !Y2 || !dY1 || !dY2 || !dX1 || !dX2 || !dparams) {
@@ -523,11 +525,14 @@ static int backward_entry(int schedule, const rev_cfg* cfg, const void* params, 
         set_error("every buffer must be 16-byte aligned"); return REV_EINVAL;
     }
     if (schedule == 1 && sv == sr) { set_error("PaReprop needs two different streams"); return REV_EINVAL; }
+    if (((uintptr_t)key_len & 3) != 0) { set_error("key_len must be 4-byte aligned"); return REV_EINVAL; }
     if (cfg->mode == REV_MODE_BF16) {
         Runner<bf16> r(*cfg, params, dparams, ws, compact);
+        r.key_len = key_len;
         return r.backward(schedule, Y1, Y2, dY1, dY2, dX1, dX2, X1o, X2o, (hipStream_t)sv, (hipStream_t)sr);
     }
     Runner<float> r(*cfg, params, dparams, ws, compact);
+    r.key_len = key_len;
     return r.backward(schedule, Y1, Y2, dY1, dY2, dX1, dX2, X1o, X2o, (hipStream_t)sv, (hipStream_t)sr);
 }
 
@@ -573,19 +578,33 @@ int64_t rev_stack_slot_bytes(const rev_cfg* cfg) {
     return make_layout(*cfg, true).slot_bytes;
 }
 
-int rev_stack_forward(const rev_cfg* cfg, const void* params, const float* X1, const float* X2, float* Y1, float* Y2,
-                      void* ws, int64_t ws_bytes, void* stream) {
+static int forward_entry(const rev_cfg* cfg, const void* params, const float* X1, const float* X2, float* Y1, float* Y2,
+                         void* ws, int64_t ws_bytes, void* stream, const int32_t* key_len) {
     RC(check_common(cfg, ws, ws_bytes, true));
     if (!params || !X1 || !X2 || !Y1 || !Y2) { set_error("a required pointer is null"); return REV_EINVAL; }
     if (!aligned16(params) || !aligned16(X1) || !aligned16(X2) || !aligned16(Y1) || !aligned16(Y2)) {
         set_error("every buffer must be 16-byte aligned"); return REV_EINVAL;
     }
+    if (((uintptr_t)key_len & 3) != 0) { set_error("key_len must be 4-byte aligned"); return REV_EINVAL; }
     if (cfg->mode == REV_MODE_BF16) {
         Runner<bf16> r(*cfg, params, nullptr, ws, true);
+        r.key_len = key_len;
         return r.forward(X1, X2, Y1, Y2, (hipStream_t)stream);
     }
     Runner<float> r(*cfg, params, nullptr, ws, true);
+    r.key_len = key_len;
     return r.forward(X1, X2, Y1, Y2, (hipStream_t)stream);
+}
+
+int rev_stack_forward(const rev_cfg* cfg, const void* params, const float* X1, const float* X2, float* Y1, float* Y2,
+                      void* ws, int64_t ws_bytes, void* stream) {
+    return forward_entry(cfg, params, X1, X2, Y1, Y2, ws, ws_bytes, stream, nullptr);
+}
+
+int rev_stack_forward_masked(const rev_cfg* cfg, const void* params, const float* X1, const float* X2,
+                             const int32_t* key_len, float* Y1, float* Y2, void* ws, int64_t ws_bytes, void* stream) {
+    if (!key_len) { set_error("key_len is null"); return REV_EINVAL; }
+    return forward_entry(cfg, params, X1, X2, Y1, Y2, ws, ws_bytes, stream, key_len);
 }
 
 int rev_stack_backward_reprop(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
@@ -599,6 +618,24 @@ int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params, const fl
                                 float* dparams, void* ws, int64_t ws_bytes, void* stream_grad, void* stream_recompute) {
     return backward_entry(1, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws, ws_bytes,
                           stream_grad, stream_recompute);
+}
+
+int rev_stack_backward_reprop_masked(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
+                                     const int32_t* key_len, const float* dY1, const float* dY2, float* dX1, float* dX2,
+                                     float* X1_out, float* X2_out, float* dparams, void* ws, int64_t ws_bytes,
+                                     void* stream) {
+    if (!key_len) { set_error("key_len is null"); return REV_EINVAL; }
+    return backward_entry(0, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws, ws_bytes, stream, stream,
+                          key_len);
+}
+
+int rev_stack_backward_pareprop_masked(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
+                                       const int32_t* key_len, const float* dY1, const float* dY2, float* dX1, float* dX2,
+                                       float* X1_out, float* X2_out, float* dparams, void* ws, int64_t ws_bytes,
+                                       void* stream_grad, void* stream_recompute) {
+    if (!key_len) { set_error("key_len is null"); return REV_EINVAL; }
+    return backward_entry(1, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws, ws_bytes,
+                          stream_grad, stream_recompute, key_len);
 }
 
 int rev_stack_backward_chain(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,

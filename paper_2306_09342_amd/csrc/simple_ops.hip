@@ -135,7 +135,8 @@ int gemm_wgrad_bf16_simple(hipStream_t s, const bf16* G, int64_t ldg, const bf16
 // Head h of token row t: q at qkv[t, h*dh], k at qkv[t, D + h*dh], v at qkv[t, 2D + h*dh].
 template <typename T>
 __global__ __launch_bounds__(256) void attn_fwd_simple(const T* __restrict__ qkv, T* __restrict__ o,
-                                                       float* __restrict__ lse, int T_, int H, int dh) {
+                                                       float* __restrict__ lse, const int* __restrict__ key_len,
+                                                       int T_, int H, int dh) {
     __shared__ float qs[4][128];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int bh = blockIdx.y, b = bh / H, h = bh % H;
@@ -149,23 +150,25 @@ __global__ __launch_bounds__(256) void attn_fwd_simple(const T* __restrict__ qkv
         for (int d = lane; d < dh; d += 64) qs[wave][d] = to_f(base[(int64_t)i * ld + d]);
     __syncthreads();
     if (!live) return;
+    // key-padding mask: keys at positions >= Tk take no part in the softmax
+    const int Tk = key_len ? min(max(key_len[b], 1), T_) : T_;
     float m = -INFINITY, l = 0.f, acc[2] = {0.f, 0.f};
-    for (int j0 = 0; j0 < T_; j0 += 64) {
+    for (int j0 = 0; j0 < Tk; j0 += 64) {
         const int j = j0 + lane;
         float s = -INFINITY;
-        if (j < T_) {
+        if (j < Tk) {
             const T* kr = base + (int64_t)j * ld + D;
             float dot = 0.f;
             for (int d = 0; d < dh; ++d) dot += qs[wave][d] * to_f(kr[d]);
             s = dot * scale;
         }
         const float mn = fmaxf(m, wave_max(s));
-        const float p = (j < T_) ? __expf(s - mn) : 0.f;
+        const float p = (j < Tk) ? __expf(s - mn) : 0.f;
         const float corr = __expf(m - mn);
         l = l * corr + wave_sum(p);
         acc[0] *= corr; acc[1] *= corr;
         m = mn;
-        const int cnt = min(64, T_ - j0);
+        const int cnt = min(64, Tk - j0);
         for (int jj = 0; jj < cnt; ++jj) {
             const float pj = __shfl(p, jj, 64);
             const T* vr = base + (int64_t)(j0 + jj) * ld + 2 * D;
@@ -184,7 +187,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_dq_simple(const T* __restrict__ qkv, const T* __restrict__ o,
                                                           const T* __restrict__ dout, const float* __restrict__ lse,
                                                           T* __restrict__ dqkv, float* __restrict__ delta,
-                                                          int T_, int H, int dh) {
+                                                          const int* __restrict__ key_len, int T_, int H, int dh) {
     __shared__ float qs[4][128];
     __shared__ float dos[4][128];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -210,11 +213,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_simple(const T* __restrict__ 
     dl = wave_sum(dl);
     const float L = lse[(int64_t)bh * T_ + i];
     if (lane == 0) delta[(int64_t)bh * T_ + i] = dl;
+    const int Tk = key_len ? min(max(key_len[b], 1), T_) : T_;
     float acc[2] = {0.f, 0.f};
-    for (int j0 = 0; j0 < T_; j0 += 64) {
+    for (int j0 = 0; j0 < Tk; j0 += 64) {
         const int j = j0 + lane;
         float ds = 0.f;
-        if (j < T_) {
+        if (j < Tk) {
             const T* kr = base + (int64_t)j * ld + D;
             const T* vr = base + (int64_t)j * ld + 2 * D;
             float dot = 0.f, dp = 0.f;
@@ -225,7 +229,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_simple(const T* __restrict__ 
             const float p = __expf(dot * scale - L);
             ds = p * (dp - dl) * scale;
         }
-        const int cnt = min(64, T_ - j0);
+        const int cnt = min(64, Tk - j0);
         for (int jj = 0; jj < cnt; ++jj) {
             const float dj = __shfl(ds, jj, 64);
             const T* kr = base + (int64_t)(j0 + jj) * ld + D;
@@ -242,7 +246,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_simple(const T* __restrict__ 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_simple(const T* __restrict__ qkv, const T* __restrict__ dout,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           T* __restrict__ dqkv, int T_, int H, int dh) {
+                                                           T* __restrict__ dqkv, const int* __restrict__ key_len,
+                                                           int T_, int H, int dh) {
     __shared__ float ks[4][128];
     __shared__ float vs[4][128];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -285,6 +290,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_simple(const T* __restrict__
             if (lane + 64 < dh) { dv[1] += pi * to_f(dr[lane + 64]); dk[1] += di * to_f(qr[lane + 64]); }
         }
     }
+    if (key_len && j >= min(max(key_len[b], 1), T_)) {          // a masked key: no query looked at it
+        dk[0] = dk[1] = dv[0] = dv[1] = 0.f;
+    }
     T* dkr = dqkv + ((int64_t)b * T_ + j) * ld + D + h * dh;
     T* dvr = dkr + D;
     if (lane < dh) { dkr[lane] = from_f<T>(dk[0]); dvr[lane] = from_f<T>(dv[0]); }
@@ -292,26 +300,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_simple(const T* __restrict__
 }
 
 template <typename T>
-int attention_forward_simple(hipStream_t s, const T* qkv, T* o, float* lse, int B, int T_, int H, int dh) {
+int attention_forward_simple(hipStream_t s, const T* qkv, T* o, float* lse, int B, int T_, int H, int dh, const int* key_len) {
     ProfScope ps(K_ATTN_FWD, s, 4.0 * B * H * (double)T_ * T_ * dh);
     dim3 grid((T_ + 3) / 4, B * H), block(256);
-    hipLaunchKernelGGL((attn_fwd_simple<T>), grid, block, 0, s, qkv, o, lse, T_, H, dh);
+    hipLaunchKernelGGL((attn_fwd_simple<T>), grid, block, 0, s, qkv, o, lse, key_len, T_, H, dh);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
 template <typename T>
 int attention_backward_simple(hipStream_t s, const T* qkv, const T* o, const T* dout, const float* lse,
-                              T* dqkv, float* delta, int B, int T_, int H, int dh) {
+                              T* dqkv, float* delta, int B, int T_, int H, int dh, const int* key_len) {
     ProfScope ps(K_ATTN_BWD, s, 8.0 * B * H * (double)T_ * T_ * dh);
     dim3 grid((T_ + 3) / 4, B * H), block(256);
-    hipLaunchKernelGGL((attn_bwd_dq_simple<T>), grid, block, 0, s, qkv, o, dout, lse, dqkv, delta, T_, H, dh);
-    hipLaunchKernelGGL((attn_bwd_dkv_simple<T>), grid, block, 0, s, qkv, dout, lse, delta, dqkv, T_, H, dh);
+    hipLaunchKernelGGL((attn_bwd_dq_simple<T>), grid, block, 0, s, qkv, o, dout, lse, dqkv, delta, key_len, T_, H, dh);
+    hipLaunchKernelGGL((attn_bwd_dkv_simple<T>), grid, block, 0, s, qkv, dout, lse, delta, dqkv, key_len, T_, H, dh);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
-template int attention_forward_simple<float>(hipStream_t, const float*, float*, float*, int, int, int, int);
-template int attention_forward_simple<bf16>(hipStream_t, const bf16*, bf16*, float*, int, int, int, int);
-template int attention_backward_simple<float>(hipStream_t, const float*, const float*, const float*, const float*, float*, float*, int, int, int, int);
-template int attention_backward_simple<bf16>(hipStream_t, const bf16*, const bf16*, const bf16*, const float*, bf16*, float*, int, int, int, int);
+template int attention_forward_simple<float>(hipStream_t, const float*, float*, float*, int, int, int, int, const int*);
+template int attention_forward_simple<bf16>(hipStream_t, const bf16*, bf16*, float*, int, int, int, int, const int*);
+template int attention_backward_simple<float>(hipStream_t, const float*, const float*, const float*, const float*, float*, float*, int, int, int, int, const int*);
+template int attention_backward_simple<bf16>(hipStream_t, const bf16*, const bf16*, const bf16*, const float*, bf16*, float*, int, int, int, int, const int*);
 
 }  // namespace rev

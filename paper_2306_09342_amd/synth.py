@@ -159,3 +159,12 @@ def make_merge_inputs(mcfg: dict, seed: int = 0):
     shapes = [(M, C), (M, C), (M // 4, 2 * C), (M // 4, 2 * C)]
     return tuple(np.random.default_rng([seed, 33, tid]).standard_normal(shp, dtype=np.float32)
                  for tid, shp in enumerate(shapes))
+
+
+def make_key_lengths(cfg: dict, seed: int = 0) -> np.ndarray:
+    """Valid lengths of a padded batch (int32 [batch]): uniform on [T/8, T], the first sample full length."""
+    T, Bn = cfg["seq_len"], cfg["batch"]
+    rng = np.random.default_rng([seed, 41])
+    lens = rng.integers(max(1, T // 8), T + 1, size=Bn).astype(np.int32)
+    lens[0] = T
+    return lens

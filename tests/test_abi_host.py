@@ -154,3 +154,23 @@ def test_merge_calls_validate_before_touching_the_device():
     assert L.rev_merge_backward(ctypes.byref(c), None, None, None, None, None, None, None, None, None, 0, None) < 0
     fake = ctypes.c_void_p(256)
     assert L.rev_merge_forward(ctypes.byref(c), fake, fake, fake, fake, fake, 16, None) == -2
+
+
+def test_masked_calls_refuse_a_null_or_misaligned_mask_on_the_host():
+    import ctypes
+    c = B.make_cfg(n_blocks=1, d_model=64, n_heads=2, d_mlp=128, seq_len=8, batch=2, mode="fp32")
+    L = B.lib()
+    fake = ctypes.c_void_p(4096)
+    ws_bytes = B.rev_stack_workspace_bytes(c)
+    rc = L.rev_stack_forward_masked(ctypes.byref(c), fake, fake, fake, None, fake, fake, fake, ws_bytes, None)
+    assert rc == -1 and "key_len" in B.rev_last_error()
+    rc = L.rev_stack_backward_reprop_masked(ctypes.byref(c), fake, fake, fake, None, fake, fake, fake, fake, None, None,
+                                            fake, fake, ws_bytes, None)
+    assert rc == -1 and "key_len" in B.rev_last_error()
+    s1, s2 = ctypes.c_void_p(8), ctypes.c_void_p(16)
+    rc = L.rev_stack_backward_pareprop_masked(ctypes.byref(c), fake, fake, fake, None, fake, fake, fake, fake, None, None,
+                                              fake, fake, ws_bytes, s1, s2)
+    assert rc == -1 and "key_len" in B.rev_last_error()
+    odd = ctypes.c_void_p(4098)
+    rc = L.rev_stack_forward_masked(ctypes.byref(c), fake, fake, fake, odd, fake, fake, fake, ws_bytes, None)
+    assert rc == -1 and "aligned" in B.rev_last_error()
