@@ -215,6 +215,13 @@ int rev_stack_backward_pareprop_masked(const rev_cfg* cfg, const void* params,
                                        void* workspace, int64_t workspace_bytes,
                                        void* stream_grad, void* stream_recompute);
 
+/* Plain stochastic gradient descent on the packed vector, theta <- theta - lr * grad
+ * (Sec. 4: the paper reports the same behaviour with SGD as with AdamW).
+ * Arguments, alignment, in-place update, optional bf16 copy and errors as for
+ * rev_adamw_step. */
+int rev_sgd_step(int64_t n, float* master, void* params_bf16, const float* grad,
+                 float lr, void* stream);
+
 /* Measurement aid for the hidden-recompute fraction: runs only one of the two
  * chains of the backward pass on `stream`.  chain = 0: the recomputation chain
  * R_N..R_1 alone (writes X1_out/X2_out if given).  chain = 1: the gradient

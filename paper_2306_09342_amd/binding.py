@@ -24,7 +24,7 @@ EXPORTS = (
     "rev_stack_workspace_bytes_reprop", "rev_stack_slot_bytes",
     "rev_stack_forward", "rev_stack_backward_reprop", "rev_stack_backward_pareprop", "rev_stack_backward_chain",
     "rev_stack_forward_masked", "rev_stack_backward_reprop_masked", "rev_stack_backward_pareprop_masked",
-    "rev_adamw_step",
+    "rev_adamw_step", "rev_sgd_step",
     "rev_merge_check_cfg", "rev_merge_param_count", "rev_merge_workspace_bytes", "rev_merge_forward", "rev_merge_backward",
     "rev_profile_begin", "rev_profile_end", "rev_profile_kinds", "rev_profile_name", "rev_profile_is_flops",
     "rev_profile_get", "rev_last_error",
@@ -87,6 +87,8 @@ def lib():
         f32 = ctypes.c_float
         L.rev_adamw_step.argtypes = [i64, vp, vp, vp, vp, vp, i32, f32, f32, f32, f32, f32, vp]
         L.rev_adamw_step.restype = ctypes.c_int
+        L.rev_sgd_step.argtypes = [i64, vp, vp, vp, f32, vp]
+        L.rev_sgd_step.restype = ctypes.c_int
         mp = ctypes.POINTER(RevMergeCfg)
         L.rev_merge_check_cfg.argtypes = [mp]
         L.rev_merge_check_cfg.restype = ctypes.c_int
@@ -289,6 +291,16 @@ def rev_adamw_step(master, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-
         assert params_bf16.numel() == master.numel()
     _check(lib().rev_adamw_step(master.numel(), _ptr(master), _ptr(params_bf16), _ptr(grad), _ptr(m), _ptr(v),
                                 int(step), lr, beta1, beta2, eps, weight_decay, _stream_handle(stream)))
+
+
+def rev_sgd_step(master, grad, lr, params_bf16=None, stream=None):
+    """In-place plain SGD update of the float32 `master` weights; `params_bf16` (optional) receives the bf16 copy."""
+    for t in (master, grad):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == master.numel()
+    if params_bf16 is not None:
+        assert params_bf16.is_cuda and params_bf16.dtype == torch.bfloat16 and params_bf16.is_contiguous()
+        assert params_bf16.numel() == master.numel()
+    _check(lib().rev_sgd_step(master.numel(), _ptr(master), _ptr(params_bf16), _ptr(grad), lr, _stream_handle(stream)))
 
 
 def make_merge_cfg(batch, grid_h, grid_w, window, d_in, mode="bf16", ln_eps=1e-5) -> RevMergeCfg:

@@ -48,6 +48,8 @@ bool profiling();
 // AdamW update of n packed elements (optimizer.hip)
 int adamw_step(hipStream_t s, int64_t n, float* master, void* params_bf16, const float* grad, float* m, float* v,
                int step, float lr, float beta1, float beta2, float eps, float weight_decay);
+// plain SGD update of n packed elements (optimizer.hip)
+int sgd_step(hipStream_t s, int64_t n, float* master, void* params_bf16, const float* grad, float lr);
 
 // ---- small device helpers ------------------------------------------------------
 __device__ __forceinline__ float to_f(float v) { return v; }

@@ -646,6 +646,16 @@ int rev_stack_backward_chain(const rev_cfg* cfg, const void* params, const float
                           ws_bytes, stream, stream);
 }
 
+int rev_sgd_step(int64_t n, float* master, void* params_bf16, const float* grad, float lr, void* stream) {
+    if (n <= 0) { set_error("sgd: n must be positive"); return REV_EINVAL; }
+    if (!master || !grad) { set_error("sgd: a required pointer is null"); return REV_EINVAL; }
+    if (!(lr >= 0.f)) { set_error("sgd: need lr >= 0"); return REV_EINVAL; }
+    if (!aligned16(master) || !aligned16(grad) || ((uintptr_t)params_bf16 & 7) != 0) {
+        set_error("sgd: float32 buffers must be 16-byte aligned, the bf16 copy 8-byte aligned"); return REV_EINVAL;
+    }
+    return sgd_step((hipStream_t)stream, n, master, params_bf16, grad, lr);
+}
+
 int rev_adamw_step(int64_t n, float* master, void* params_bf16, const float* grad, float* m, float* v,
                    int32_t step, float lr, float beta1, float beta2, float eps, float weight_decay, void* stream) {
     if (n <= 0) { set_error("adamw: n must be positive"); return REV_EINVAL; }

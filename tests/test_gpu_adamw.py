@@ -110,3 +110,28 @@ def test_three_training_steps_match_the_oracle_pipeline(mode):
         # AdamW normalises the gradient, so a relative gradient error eps moves a weight by about lr * eps
         # of a full step; the bound is the backward tolerance of the mode
         assert e <= TOL[mode], (step, e)
+
+
+@pytest.mark.parametrize("n", [7, 4096, 1000003])
+@pytest.mark.parametrize("with_bf16", [False, True])
+def test_sgd_steps_match_the_oracle(n, with_bf16):
+    print(f"[case] sgd n={n} bf16_copy={with_bf16}", flush=True)
+    rng = np.random.default_rng([n, 9, int(with_bf16)])
+    theta = (0.02 * rng.standard_normal(n)).astype(np.float32)
+    lr = float(np.float32(3e-2))
+    master = torch.from_numpy(theta.copy()).cuda()
+    pb = torch.empty(n, dtype=torch.bfloat16, device="cuda") if with_bf16 else None
+    ref = theta.astype(np.float64)
+    for step in range(3):
+        g = rng.standard_normal(n).astype(np.float32)
+        gd = torch.from_numpy(g).cuda()
+        B.rev_sgd_step(master, gd, lr, params_bf16=pb)
+        torch.cuda.synchronize()
+        ref = A.sgd_step(ref, g, lr)
+        e = rel_err(master.cpu().numpy(), ref)
+        assert e <= TOL, (step, e)
+        if with_bf16:
+            assert torch.equal(pb, master.to(torch.bfloat16)), "bf16 copy is not the rounded master"
+    t = torch.zeros(8, device="cuda")
+    with pytest.raises(B.RevError):
+        B.rev_sgd_step(t, t.clone(), -1.0)
