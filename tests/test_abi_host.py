@@ -174,3 +174,10 @@ def test_masked_calls_refuse_a_null_or_misaligned_mask_on_the_host():
     odd = ctypes.c_void_p(4098)
     rc = L.rev_stack_forward_masked(ctypes.byref(c), fake, fake, fake, odd, fake, fake, fake, ws_bytes, None)
     assert rc == -1 and "aligned" in B.rev_last_error()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
