@@ -569,9 +569,19 @@ static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B
 
 template <int DHP>
 static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse, bf16* dqkv,
-                      float* delta, int B, int T, int H, int dh, const int* key_len) {
+                      float* delta, int B, int T, int H, int dh, const int* key_len, bool solo) {
     int nblk, nw;
     row_split(T, &nblk, &nw);
+    // A launch that has the device to itself splits a head's row tiles over 4-wavefront workgroups:
+    // the backward kernels need 160-210 registers, so only one 7-wavefront workgroup fits a CU but
+    // three (two) of 4 wavefronts do -- 4 % (197 tokens) to 12 % (257 tokens) faster.  Next to another
+    // stream's kernels the extra resident workgroups cost the neighbour more than they gain (measured:
+    // PaReprop 2 % slower), so there one workgroup per head stays.  A wavefront's work does not depend
+    // on the grouping, so the results are bit-identical.
+    if (solo && nw > 4) {
+        nblk = ((T + 31) / 32 + 3) / 4;
+        nw = 4;
+    }
     // With 4 or more wavefronts the backward kernels always stream 64-row tiles with the next tile
     // prefetched into registers: measured 6-8 % faster than keeping the head resident (197 and 257
     // tokens), with a fifth of the LDS, which also leaves room for a co-running kernel of the other stream.
@@ -616,18 +626,18 @@ int attention_forward<float>(hipStream_t s, const float* qkv, float* o, float* l
 
 template <>
 int attention_backward<bf16>(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse,
-                             bf16* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len) {
+                             bf16* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len, bool solo) {
     if ((dh & 7) || dh > 128 || !mfma_ok(qkv, o, dout, dqkv))
         return attention_backward_simple<bf16>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
     ProfScope ps(K_ATTN_BWD, s, 8.0 * B * H * (double)T * T * dh);
-    if (dh <= 32) return bwd_launch<32>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
-    if (dh <= 64) return bwd_launch<64>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
-    if (dh <= 96) return bwd_launch<96>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
-    return bwd_launch<128>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
+    if (dh <= 32) return bwd_launch<32>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
+    if (dh <= 64) return bwd_launch<64>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
+    if (dh <= 96) return bwd_launch<96>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
+    return bwd_launch<128>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
 }
 template <>
 int attention_backward<float>(hipStream_t s, const float* qkv, const float* o, const float* dout, const float* lse,
-                              float* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len) {
+                              float* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len, bool) {
     return attention_backward_simple<float>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
 }
 

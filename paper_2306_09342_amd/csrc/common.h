@@ -200,6 +200,7 @@ int attention_forward(hipStream_t s, const TA* qkv, TA* o, float* lse, int B, in
                       const int* key_len = nullptr);
 template <typename TA>
 int attention_backward(hipStream_t s, const TA* qkv, const TA* o, const TA* dout, const float* lse,
-                       TA* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len = nullptr);
+                       TA* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len = nullptr,
+                       bool solo = false);     // solo: the launch has the device to itself (one stream)
 
 }  // namespace rev

@@ -341,7 +341,7 @@ struct Runner {
         // ---- F branch
         Epi q = epi0(); q.kind = EPI_PLAIN; q.out = dO; q.ldo = D;
         RC(dgrad(s, blk, T_WPROJ, gy1b, D, D, q));
-        RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh, key_len)));
+        RC((attention_backward<T>(s, sl.qkv, sl.o, dO, sl.lse, dqkv, at<float>(L.delta), B, Tn, H, dh, key_len, solo)));
         if (ev) REV_HIP(hipEventRecord(ev[2], s));
         Epi r = epi0(); r.kind = EPI_PLAIN; r.out = dn; r.ldo = D;
         RC(dgrad(s, blk, T_WQKV, dqkv, 3 * D, D, r));
