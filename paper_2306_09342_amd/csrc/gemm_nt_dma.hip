@@ -198,7 +198,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     // With one wavefront per SIMD the loads of the next stage are handed out in slices between the
     // product groups of the current one, so the matrix cores start right after the barrier.
     constexpr bool SPREAD = (NW == 4 && TM * TN >= 16 && NS == 2 && LPW % (BK / 16) == 0);
-    constexpr bool HANDPLACED_SHAPE = (TM == 2 && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
+    // 64x64 per wavefront (four wavefronts, the default 128x128 tile) or 160x64 (two wavefronts, the tall tile)
+    constexpr bool HANDPLACED_SHAPE = (((TM == 2 && NW == 4) || (TM == 5 && NW == 2)) && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
 
     // Epilogue geometry (a wavefront's 32-row panels leave through LDS in full rows) and, for the
     // epilogues that read a second operand (residual stream, saved pre-activation), that operand:
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int n = n0 + wn * CW + 4 * c4;
     // (float32 residual rows cost 4 registers each: only the first panel's are held across the main
     // loop, the second panel's are requested when the epilogue starts)
-    constexpr int PRE = !HANDPLACED_SHAPE ? 0 : (KIND == EPI_GELU_BWD ? TM : (KIND == EPI_RESIDUAL ? 1 : 0));
+    constexpr int PRE = !HANDPLACED_SHAPE ? 0 : (KIND == EPI_GELU_BWD ? (TM > 2 ? 2 : TM) : (KIND == EPI_RESIDUAL ? 1 : 0));
     f32x4_t opnd_pre[TM][NP];
     if (PRE > 0 && n < N) {
 #pragma unroll
@@ -243,7 +244,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int a_row = (wm * TM * 32 + fr) * ROWB;
     const int b_row = A_BYTES + (wn * TN * 32 + fr) * ROWB;
 
-    // The default shape (128x128x64 tile, 64x64 per wavefront, 2 stages) takes the hand-placed path.
+    // The default shape (128x128x64 tile, 64x64 per wavefront, 2 stages) and the tall one (160x128x64, 160x64 per
+    // wavefront) take the hand-placed path.
     constexpr bool HANDPLACED = HANDPLACED_SHAPE;
     if constexpr (HANDPLACED) {
         const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(unsigned char, smem);
@@ -281,11 +283,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             constexpr bool has_next = decltype(next_tag)::value;
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __builtin_amdgcn_s_barrier();
-            u32x4_t a[4][2], b[4][2];
+            u32x4_t a[4][TM], b[4][2];
             auto read_group = [&](auto kk_tag) {
                 constexpr int kk = decltype(kk_tag)::value;
                 a[kk][0] = lds_read_b128(a_addr[kk], SOFF);
                 a[kk][1] = lds_read_b128(a_addr[kk], SOFF + 32 * ROWB);
+                if constexpr (TM == 5) {
+                    a[kk][2] = lds_read_b128(a_addr[kk], SOFF + 64 * ROWB);
+                    a[kk][3] = lds_read_b128(a_addr[kk], SOFF + 96 * ROWB);
+                    a[kk][4] = lds_read_b128(a_addr[kk], SOFF + 128 * ROWB);
+                }
                 if (BKM) {
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
@@ -300,24 +307,31 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) acc[j][i] = mfma32(as_bf16x8(b[kk][j]), as_bf16x8(a[kk][i]), acc[j][i]);
+                    for (int i = 0; i < TM; ++i) acc[j][i] = mfma32(as_bf16x8(b[kk][j]), as_bf16x8(a[kk][i]), acc[j][i]);
                 __builtin_amdgcn_sched_barrier(0);       // the products stay between their wait and the next one
+            };
+            // waits until at most N younger LDS reads are outstanding; carries step kk's fragments
+            auto wait_group = [&](auto n_tag, int kk) {
+                constexpr int N = decltype(n_tag)::value;
+                if constexpr (TM == 5) lds_wait7<N>(a[kk][0], a[kk][1], a[kk][2], a[kk][3], a[kk][4], b[kk][0], b[kk][1]);
+                else lds_wait4<N>(a[kk][0], a[kk][1], b[kk][0], b[kk][1]);
             };
             using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
             using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
-            constexpr int RPK = BKM ? 6 : 4;              // LDS reads per step
+            constexpr int RPK = TM + (BKM ? 4 : 2);       // LDS reads per step
+            using NRPK = std::integral_constant<int, RPK>; using N0 = std::integral_constant<int, 0>;
             // one step ahead, as the compiler would order it, but every product group waits only for
             // its own operands (the reads of the step after it stay in flight)
             read_group(I0{}); read_group(I1{});
 #if !defined(REV_EXP_NOLOAD)
             if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
 #endif
-            lds_wait4<RPK>(a[0][0], a[0][1], b[0][0], b[0][1]); products(0);
+            wait_group(NRPK{}, 0); products(0);
             read_group(I2{});
-            lds_wait4<RPK>(a[1][0], a[1][1], b[1][0], b[1][1]); products(1);
+            wait_group(NRPK{}, 1); products(1);
             read_group(I3{});
-            lds_wait4<RPK>(a[2][0], a[2][1], b[2][0], b[2][1]); products(2);
-            lds_wait4<0>(a[3][0], a[3][1], b[3][0], b[3][1]);   products(3);
+            wait_group(NRPK{}, 2); products(2);
+            wait_group(N0{}, 3);   products(3);
         };
         using S0 = std::integral_constant<int, 0>; using S1 = std::integral_constant<int, 1>;
         int kt = 0;
@@ -534,15 +548,11 @@ static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B
             // 160-row tiles (two wavefronts of 160x64) when they turn a short ragged second round of
             // 128-row tiles into a single round.  Only for launches that have the device to themselves:
             // next to another stream's kernels that round is filled anyway and the larger LDS footprint
-            // keeps the neighbour out (measured: +2.4 % sequential, -5 % parallel schedule).  Never with
-            // fused column sums (their strips are 64 rows), and not for the input-gradient form (weights
-            // read through the LDS transpose read): there the compiler-placed reads of the tall tile lose
-            // to the hand-placed 128x128 loop (63.8 against 60.4 us per launch).  Each output element sums the same products
-            // in the same order under either shape, so the choice does not change a bit of the result.
-            if constexpr (!BKM) {
-                if (g_nt_variant != 1 && epi.solo && epi.colsum == nullptr && tall_tiles_pay(M, N))
-                    return launch_dma<160, 128, 1, 2, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
-            }
+            // keeps the neighbour out (measured: sequential schedule faster, parallel schedule 5 % slower).
+            // Never with fused column sums (their strips are 64 rows).  Each output element sums the same
+            // products in the same order under either shape, so the choice does not change a bit of the result.
+            if (g_nt_variant != 1 && epi.solo && epi.colsum == nullptr && tall_tiles_pay(M, N))
+                return launch_dma<160, 128, 1, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
             return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
     }
 }

@@ -83,6 +83,11 @@ template <int N>
 __device__ __forceinline__ void lds_wait4(u32x4_t& a0, u32x4_t& a1, u32x4_t& b0, u32x4_t& b1) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1) : "n"(N));
 }
+template <int N>
+__device__ __forceinline__ void lds_wait7(u32x4_t& a0, u32x4_t& a1, u32x4_t& a2, u32x4_t& a3, u32x4_t& a4, u32x4_t& b0,
+                                          u32x4_t& b1) {
+    asm volatile("s_waitcnt lgkmcnt(%7)" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(a4), "+v"(b0), "+v"(b1) : "n"(N));
+}
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) { return __builtin_bit_cast(bf16x8_t, v); }
 __device__ __forceinline__ u32x4_t join64(u32x2_t lo, u32x2_t hi) { return u32x4_t{lo[0], lo[1], hi[0], hi[1]}; }
 
