@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # Fabric-side bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter
 # reads for a plain 256 MiB device copy), averaged over the launches of the kernel family; measured
 # offline with the commands in profiles/vit_b_backward_reprop_hbm_traffic_pmc.txt.
-MEASURED_TRAFFIC_BYTES = {"vit_b": {"gemm_nt": 1.792e8}}
+MEASURED_TRAFFIC_BYTES = {"vit_b": {"gemm_nt": 1.709e8}}
 
 
 def algorithmic_flops(cfg):
