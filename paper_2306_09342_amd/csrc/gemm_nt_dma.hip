@@ -19,6 +19,12 @@
 // lane's accumulator quad holds 4 consecutive output columns; the tile goes
 // through LDS once and leaves in full contiguous rows with 16-byte accesses,
 // the epilogue (bias, GELU, GELU', residual) applied on the way out.
+//
+// Two tile shapes run the tuned loop: 128x128 with four wavefronts of 64x64 (two
+// workgroups per CU, the general case) and 160x128 with two wavefronts of 160x64
+// (7 fragment reads per 10 products, one wavefront per SIMD), which a launch that
+// has the device to itself picks when 128-row tiles would leave a short, ragged
+// last round of workgroups.
 #include "mfma.h"
 #include <type_traits>
 
