@@ -27,10 +27,23 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 PEAK_FP32_TFLOPS = 157.3      # vector/matrix fp32
 PEAK_HBM_GBS = 8000.0
 
-# Fabric-side bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter
-# reads for a plain 256 MiB device copy), averaged over the launches of the kernel family; measured
-# offline with the commands in profiles/vit_b_backward_reprop_hbm_traffic_pmc.txt.
-MEASURED_TRAFFIC_BYTES = {"vit_b": {"gemm_nt": 1.709e8}}
+
+
+def profiled_traffic(workload, family):
+    """Fabric-side bytes per launch of a kernel family (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what
+    the same counter reads for a plain 256 MiB device copy), read from the tracked counter summary of this
+    workload: profiles/<workload>_backward_reprop_hbm_traffic_pmc.txt, whose header holds the two profiler
+    commands.  It is an offline measurement, so the source file travels with the value; (None, None) when no
+    summary of this workload and family is tracked."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{workload}_backward_reprop_hbm_traffic_pmc.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, None
+    m = re.search(rf"^{re.escape(family)} family:.*=\s*([0-9.eE+-]+)\s*bytes", text, flags=re.M)
+    return (float(m.group(1)), os.path.relpath(path, ROOT)) if m else (None, None)
+
 
 
 def algorithmic_flops(cfg):
@@ -248,6 +261,50 @@ def bench_hierarchy(args, hier, B, synth, torch, np):
         "stages": per_stage}))
 
 
+def both_schedules(name, B, synth, torch, np, steps, warmup):
+    """PaReprop and Reprop backward passes of one workload: samples/s of each, their ratio and the share of the
+    bf16 (fp32 for the tiny workload) peak over the whole pass."""
+    cfg = dict(synth.CONFIGS[name])
+    c = B.make_cfg(**cfg)
+    params = torch.from_numpy(synth.make_params(cfg, seed=0)).cuda().to(B.param_dtype(c))
+    x, dy1, dy2 = synth.make_inputs(cfg, seed=0)
+    X, dY1, dY2 = (torch.from_numpy(a).cuda() for a in (x, dy1, dy2))
+    ws = B.alloc_workspace(c)
+    Y1, Y2 = B.rev_stack_forward(c, params, X, X, workspace=ws)
+    main_s = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    out = {}
+    out.update(B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws))
+    torch.cuda.synchronize()
+    med = {}
+    for sched, fn in (("pareprop", lambda: B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, side,
+                                                                          workspace=ws, out=out)),
+                      ("reprop", lambda: B.rev_stack_backward_reprop(c, params, Y1, Y2, dY1, dY2, workspace=ws, out=out))):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = []
+        for _ in range(steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main_s)
+            fn()
+            e1.record(main_s)
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        med[sched] = float(np.median([a.elapsed_time(z) for a, z in ev]))
+    peak = PEAK_BF16_TFLOPS if cfg["mode"] == "bf16" else PEAK_FP32_TFLOPS
+    flops = algorithmic_flops(cfg)
+    res = {"workload": f"{cfg['n_blocks']} blocks, D={cfg['d_model']}, H={cfg['n_heads']}, Dm={cfg['d_mlp']}, "
+                       f"T={cfg['seq_len']}, batch={cfg['batch']}, {cfg['mode']}",
+           "pareprop": cfg["batch"] / (med["pareprop"] * 1e-3), "reprop": cfg["batch"] / (med["reprop"] * 1e-3),
+           "pareprop_ms": med["pareprop"], "reprop_ms": med["reprop"], "ratio": med["reprop"] / med["pareprop"],
+           "mfma_fraction_whole_path": flops / (med["pareprop"] * 1e-3) / (peak * 1e12),
+           "finite": bool(torch.isfinite(out["dparams"]).all().item())}
+    del ws, X, dY1, dY2, Y1, Y2, out, params
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -257,6 +314,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["all", "reprop", "pareprop"], default="all",
                     help="restrict the run to one schedule (for profiler runs); the JSON line then lacks the other")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short both-schedules runs on the other workloads")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples the oracle is timed on (0 = auto)")
     ap.add_argument("--sweep-batch", default="",
                     help="comma-separated batch sizes: time both schedules and report workspace bytes at each "
@@ -403,6 +462,7 @@ def main():
     dom = max((k for k in families), key=lambda k: families[k]["ms_per_step"])
     ms_d, n_d, work_d, is_flops_d = fam[dom]
     achieved = work_d / (ms_d * 1e-3) / (1e12 if is_flops_d else 1e9)
+    traffic, traffic_src = profiled_traffic(args.workload, dom)
     roofline = {
         "kernel": dom,
         "bound": "mfma" if is_flops_d else "hbm",
@@ -412,7 +472,8 @@ def main():
         "frac": achieved / (peak if is_flops_d else PEAK_HBM_GBS),
         "avg_launch_ms": ms_d / n_d,
         "work_per_launch": work_d / n_d,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dom),
+        "traffic": traffic,
+        "traffic_source": traffic_src,
         "launches_per_step": n_d / prof_steps,
         "note": "family average over all launches of the dominant kernel family in a Reprop pass, each "
                 "bracketed by HIP events on its own stream",
@@ -437,6 +498,9 @@ def main():
         "pareprop_over_reprop": value / reprop_value,
         "recompute_chain_ms": float(np.median(ms_rc)), "gradient_chain_ms": float(np.median(ms_vc)),
         "hidden_recompute_fraction": hidden,
+        # the longer chain alone bounds the parallel schedule from below; what the pass takes beyond it is the
+        # part of the shorter chain that is still exposed
+        "exposed_beyond_longer_chain_ms": float(np.median(ms_p)) - max(float(np.median(ms_rc)), float(np.median(ms_vc))),
         "algorithmic_tflop_per_step": flops / 1e12,
         "mfma_fraction_whole_path": {"pareprop": flops / (float(np.median(ms_p)) * 1e-3) / (peak * 1e12),
                                      "reprop": flops / (float(np.median(ms_r)) * 1e-3) / (peak * 1e12)},
@@ -448,6 +512,13 @@ def main():
         "paper_context": "paper reports whole-training-step gains only (A100 80GB, precision unstated): ViT ~0%, "
                          "up to +20% on Swin; no backward-only number",
     }
+
+    # ---- both schedules on the other workloads of the comparison (shorter runs; the headline stays the
+    # workload named above)
+    if args.workload == "vit_b" and not args.no_other_configs:
+        line["other_configs"] = {}
+        for name in ("tiny", "vit_s", "roberta_base", "vit_h"):
+            line["other_configs"][name] = both_schedules(name, B, synth, torch, np, steps=20, warmup=5)
 
     # ---- whole training step (the quantity the paper's throughput figures are about): forward of
     # the stack, reversible backward, AdamW update of every parameter; dY stays the fixed synthetic

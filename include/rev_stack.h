@@ -13,8 +13,10 @@
  *
  * Readings the paper leaves open: LayerNorm sits inside each branch (pre-LN),
  * uses the biased variance and eps = cfg.ln_eps; attention is softmax(q k^T /
- * sqrt(head_dim)) v with no mask and no dropout; GELU is the exact erf form;
- * every linear map has a bias.
+ * sqrt(head_dim)) v with no mask and no dropout; GELU is the erf form x*Phi(x)
+ * (REV_MODE_FP32 evaluates erf; REV_MODE_BF16 evaluates Phi with a fitted
+ * polynomial of absolute error < 6.5e-5 on |x| <= 3.8 and takes exactly 0 / 1
+ * beyond); every linear map has a bias.
  *
  * All pointers except `cfg` are DEVICE pointers owned by the caller; the library
  * allocates no device memory, frees none, and keeps no state between calls
@@ -22,8 +24,11 @@
  * return the work is ordered before anything enqueued later on the stream the
  * call was given (for the PaReprop entry: on `stream_grad`).  Inputs are never
  * written.  Outputs and the workspace are fully overwritten; they must not
- * overlap each other or the inputs.  Concurrent calls must use different
- * workspaces.
+ * overlap each other or the inputs.  Calls may be issued concurrently from
+ * several host threads as long as every call in flight has its own workspace,
+ * its own streams and its own outputs (each two-stream call leases its own set
+ * of events from the pool); the rev_profile_* calls are the exception and are
+ * not thread safe.
  *
  * Layouts.  Activations and cotangents X1, X2, Y1, Y2, dY1, dY2, dX1, dX2 are
  * float32, row-major [batch, seq_len, d_model] (token-major, features
@@ -47,7 +52,8 @@
  * Limits (anything else returns REV_EINVAL before any work is enqueued):
  * all six sizes positive; d_model % n_heads == 0; d_model % 8 == 0;
  * d_mlp % 8 == 0; head_dim % 8 == 0 and head_dim <= 128; d_model <= 8192;
- * d_mlp <= 32768; batch*seq_len < 2^24.
+ * d_mlp <= 32768; batch*seq_len <= 4194240 and batch*n_heads <= 65535 (launch-
+ * grid limits).
  *
  * Errors.  Every int-returning call returns REV_OK (0) or a negative code; the
  * text of the last failure on the calling thread is returned by

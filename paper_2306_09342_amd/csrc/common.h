@@ -5,6 +5,7 @@
 #include <stdint.h>
 #include <string>
 #include <cmath>
+#include <atomic>
 
 #include "rev_stack.h"
 
@@ -21,6 +22,19 @@ int  hip_fail(hipError_t e, const char* what, const char* file, int line);
         hipError_t _e = (expr);                                              \
         if (_e != hipSuccess) return ::rev::hip_fail(_e, #expr, __FILE__, __LINE__); \
     } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per process.  Callable from several host threads: the runtime call is
+// idempotent and the flag is published only after it has succeeded, so whoever finds it set may launch.
+struct LdsLimit {
+    std::atomic<bool> done{false};
+    int ensure(const void* kern, int bytes) {
+        if (done.load(std::memory_order_acquire)) return 0;
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(MaxDynamicSharedMemorySize)", __FILE__, __LINE__);
+        done.store(true, std::memory_order_release);
+        return 0;
+    }
+};
 
 // ---- kernel families for the per-family timing ------------------------------
 enum Kind {

@@ -344,11 +344,8 @@ int ln_backward(hipStream_t s, const TA* dn, const float* x, const float* stats,
             auto kern = ln_bwd_kernel<TA, TP, J>;                                                                       \
             constexpr int copies = LnBwdCfg<J>::ACC_LDS ? 4 : 1;                                                        \
             const size_t shmem = (size_t)copies * 3 * D * sizeof(float);                                                \
-            static bool attr_set = false;                                                                               \
-            if (!attr_set) {                                                                                            \
-                REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, copies * 3 * 64 * J * 16)); \
-                attr_set = true;                                                                                        \
-            }                                                                                                           \
+            static LdsLimit lim;                                                                                        \
+            if (int rc = lim.ensure(reinterpret_cast<const void*>(kern), copies * 3 * 64 * J * 16)) return rc;          \
             hipLaunchKernelGGL(kern, grid, block, shmem, s, dn, x, stats, g, r, out, outb, partial, M, D, rpb);     \
         } break;
             CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(8) CASE(12) CASE(16) CASE(24) CASE(32)

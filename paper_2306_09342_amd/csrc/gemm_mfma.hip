@@ -151,12 +151,9 @@ template <int BM, int BN, int WM, int WN, int KIND>
 static int launch_nt(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                      const Epi& epi) {
     constexpr size_t shmem = (size_t)2 * (BM + BN) * NT_LDP * sizeof(uint16_t);
-    static bool attr_set = false;
+    static LdsLimit lim;
     auto kern = gemm_nt_kernel<BM, BN, WM, WN, KIND>;
-    if (!attr_set) {
-        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
-        attr_set = true;
-    }
+    if (int rc = lim.ensure(reinterpret_cast<const void*>(kern), (int)shmem)) return rc;
     const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(WM * WN * 64), shmem, s, A, lda, B, ldb, M, N, K, epi);
     REV_HIP(hipGetLastError());

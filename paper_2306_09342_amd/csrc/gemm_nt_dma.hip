@@ -29,16 +29,13 @@
 #include "mfma.h"
 #include <type_traits>
 
-// Compile-time switches for timing experiments only (never defined in the library build): REV_EXP_NOLOAD
-// leaves out the global loads of the main loop, REV_EXP_NOCOMPUTE its products (generic path), REV_EXP_NOEPI
-// the epilogue, so that the cost of each part can be read off a stand-alone run; REV_TUNE_VARIANTS adds the
-// tile shapes that were measured against the default one and rejected.
-
 namespace rev {
 
-// Normal CDF for the bf16 GELU epilogues: Phi(x) = 1/2 + x * P(x^2) on |x| <= 3.8, clamped outside, with a
-// degree-6 minimax-fitted P (|error| < 6.5e-5, below half a bf16 ulp of the value the epilogue
-// stores); plain FMAs, no transcendental.  The density, needed by the derivative only, is one exp.
+// Normal CDF for the bf16 GELU epilogues: Phi(x) = 1/2 + x * P(x^2) on |x| <= 3.8 with a degree-6 minimax-fitted P
+// (absolute error < 6.5e-5 there; plain FMAs, no transcendental), and exactly 0 / 1 beyond, so that gelu(x) is exactly
+// 0 for x < -3.8 (the true value is below 2.8e-4 in magnitude and shrinking) and exactly x for x > 3.8.  The bound is an
+// absolute one: relative to the small negative-tail values of gelu it is not small (4.6 % at x = -3).
+// The density, needed by the derivative only, is one exp.
 __device__ __forceinline__ float gelu_cdf(float x) {
     const float xc = fminf(fmaxf(x, -3.8f), 3.8f);
     const float u = xc * xc;
@@ -49,7 +46,10 @@ __device__ __forceinline__ float gelu_cdf(float x) {
     p = p * u + 9.316634387e-03f;
     p = p * u - 6.571978331e-02f;
     p = p * u + 3.986767530e-01f;
-    return 0.5f + xc * p;
+    float r = 0.5f + xc * p;
+    r = x < -3.8f ? 0.f : r;
+    r = x > 3.8f ? 1.f : r;
+    return r;
 }
 __device__ __forceinline__ float gelu_pdf(float x) { return 0.39894228040143268f * __expf(-0.5f * x * x); }
 
@@ -330,9 +330,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             // one step ahead, as the compiler would order it, but every product group waits only for
             // its own operands (the reads of the step after it stay in flight)
             read_group(I0{}); read_group(I1{});
-#if !defined(REV_EXP_NOLOAD)
             if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
-#endif
             wait_group(NRPK{}, 0); products(0);
             read_group(I2{});
             wait_group(NRPK{}, 1); products(1);
@@ -358,9 +356,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             // single buffer: latency is hidden by the other workgroups resident on the CU
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __builtin_amdgcn_s_barrier();                 // everybody is done reading the buffer
-#if !defined(REV_EXP_NOLOAD)
             issue(kt, 0);
-#endif
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __builtin_amdgcn_s_barrier();
         } else {
@@ -368,14 +364,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             if (kt + NS - 2 < nk) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NS > 1 ? (NS - 2) * LPW : 0));
             else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __builtin_amdgcn_s_barrier();
-#if !defined(REV_EXP_NOLOAD)
             if (!SPREAD && kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
-#endif
         }
         const unsigned char* st = smem + (kt % NS) * STAGE;
-#if defined(REV_EXP_NOCOMPUTE)
-        if (kt >= 0) continue;
-#endif
         // fragments of step kk+1 are requested before the products of step kk are issued
         bf16x8_t a[2][TM], b[2][TN];
         auto load_frags = [&](int kk, int slot) {
@@ -392,12 +383,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
-#if !defined(REV_EXP_NOLOAD)
             if (SPREAD && kt + 1 < nk) {
                 constexpr int PER = LPW / (BK / 16);
                 issue_part(kt + 1, (kt + 1) % NS, kk * PER, (kk + 1) * PER);
             }
-#endif
             __builtin_amdgcn_sched_barrier(0);       // keep the LDS reads ahead of the products that hide them
 #pragma unroll
             for (int j = 0; j < TN; ++j)
@@ -407,19 +396,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
         }
     }
 
-#if defined(REV_EXP_NOEPI)
-    {   // timing experiment: keep the accumulators alive, store (almost) nothing
-        float sacc = 0.f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sacc += acc[j][i][v];
-        if (sacc == 12345.678f && epi.outf) epi.outf[0] = sacc;
-        return;
-    }
-#endif
     // ---- epilogue through LDS, 32 rows at a time: wavefront-private [32][TN*32 + 4] float32 ----
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
     __builtin_amdgcn_s_barrier();                         // every wavefront is done with the operand stages
@@ -477,8 +453,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     }
 }
 
-int g_nt_group = 0;     // tuning hook: n-tiles per column group (0 = automatic)
-
 template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 static int launch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                       const Epi& epi) {
@@ -486,33 +460,24 @@ static int launch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, 
     constexpr size_t stage_bytes = (size_t)NS * (BM + BN) * BK * 2;
     constexpr size_t epi_bytes = (size_t)NW * 32 * (BN / WN + 4) * 4;
     constexpr size_t shmem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
-    static bool attr_set = false;
+    static LdsLimit lim;
     auto kern = gemm_nt_dma_kernel<BM, BN, WM, WN, BK, NS, KIND, BKM>;
-    if (!attr_set) {
-        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
-        attr_set = true;
-    }
+    if (int rc = lim.ensure(reinterpret_cast<const void*>(kern), (int)shmem)) return rc;
     const int tiles_n = (N + BN - 1) / BN;
     const int tiles = ((M + BM - 1) / BM) * tiles_n;
     // Group width.  An XCD runs about 64 tiles at a time; with at most 8 n-tiles per group it holds 8 or
     // more m-rows of the group at once, all sweeping the same k-slices of the same slice of B, which
     // therefore stays in L2 (measured: L2 misses of the 24-n-tile GEMMs halve).  Narrow outputs
     // (up to 12 n-tiles) are left ungrouped: re-reading A once per group would cost more than it saves.
-    int gn = g_nt_group > 0 ? g_nt_group : (tiles_n <= 12 ? tiles_n : 8);
-    if (gn > tiles_n) gn = tiles_n;
+    const int gn = tiles_n <= 12 ? tiles_n : 8;
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * 64), shmem, s, A, lda, B, ldb, M, N, K, epi, gn);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }
 
-int g_nt_variant = 0;   // tuning hook: tile shape of the pipelined NT GEMM (0 = automatic, 1 = 128x128 always)
-
 // number of 64-row strips whose column sums the EPI_GELU_BWD epilogue writes (whole tiles, so every
 // strip of every launched workgroup is written, those past M with zeros)
 int gemm_colsum_strips(int M) {
-#ifdef REV_TUNE_VARIANTS
-    if (g_nt_variant == 2) return ((M + 255) / 256) * 4;
-#endif
     return ((M + 127) / 128) * 2;
 }
 
@@ -537,38 +502,22 @@ static bool tall_tiles_pay(int M, int N) {
 template <int KIND, bool BKM>
 static int dispatch_dma(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                         const Epi& epi) {
-    switch (g_nt_variant) {
-#ifdef REV_TUNE_VARIANTS
-        case 2: return launch_dma<256, 128, 4, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-        case 34: return launch_dma<128, 128, 2, 2, 32, 4, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
-        case 35: return launch_dma<128, 128, 2, 2, 32, 3, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
-        case 20: return launch_dma<128, 128, 2, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-        case 25: return launch_dma<256, 128, 4, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-        case 27: return launch_dma<256, 256, 2, 2, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
-        case 28: return launch_dma<256, 128, 2, 1, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
-        case 26: return launch_dma<256, 128, 2, 2, 64, 1, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-        case 21: return launch_dma<128, 128, 2, 2, 64, 3, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-        case 22: return launch_dma<128, 128, 2, 2, 64, 4, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-        case 23: return launch_dma<256, 256, 2, 4, 64, 2, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
-        case 24: return launch_dma<256, 256, 2, 4, 32, 4, KIND, false>(s, A, lda, B, ldb, M, N, K, epi);
-#endif
-        default:
-            // K a multiple of 32 but not of 64 (e.g. width 96): the same tile with 32-wide stages
-            if (K % 64 != 0) return launch_dma<128, 128, 2, 2, 32, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-            // 160-row tiles (two wavefronts of 160x64) when they turn a short ragged second round of
-            // 128-row tiles into a single round.  Only for launches that have the device to themselves:
-            // next to another stream's kernels that round is filled anyway and the larger LDS footprint
-            // keeps the neighbour out (measured: sequential schedule faster, parallel schedule 5 % slower).
-            // Never with fused column sums (their strips are 64 rows).  Each output element sums the same
-            // products in the same order under either shape, so the choice does not change a bit of the result.
-            // Small launches (at most one 128-row tile for every second CU): 64x128 tiles run by two
-            // wavefronts of 64x64 put twice as many workgroups on the chip (8-13 % faster at 197...1576 rows)
-            if (g_nt_variant != 1 && epi.colsum == nullptr && ((M + 127) / 128) * ((N + 127) / 128) <= 128)
-                return launch_dma<64, 128, 1, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-            if (g_nt_variant != 1 && epi.solo && epi.colsum == nullptr && tall_tiles_pay(M, N))
-                return launch_dma<160, 128, 1, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-            return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
-    }
+    // K a multiple of 32 but not of 64 (e.g. width 96): the same tile with 32-wide stages
+    if (K % 64 != 0) return launch_dma<128, 128, 2, 2, 32, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+    // Small launches (at most one 128-row tile for every second CU): 64x128 tiles run by two
+    // wavefronts of 64x64 put twice as many workgroups on the chip (8-13 % faster at 197...1576 rows).
+    // Never with fused column sums (their strips belong to 128-row tiles).
+    if (epi.colsum == nullptr && ((M + 127) / 128) * ((N + 127) / 128) <= 128)
+        return launch_dma<64, 128, 1, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+    // 160-row tiles (two wavefronts of 160x64) when they turn a short ragged second round of
+    // 128-row tiles into a single round.  Only for launches that have the device to themselves:
+    // next to another stream's kernels that round is filled anyway and the larger LDS footprint
+    // keeps the neighbour out (measured: sequential schedule faster, parallel schedule 5 % slower).
+    // Each output element sums the same products in the same order under every shape, so the choice
+    // does not change a bit of the result.
+    if (epi.solo && epi.colsum == nullptr && tall_tiles_pay(M, N))
+        return launch_dma<160, 128, 1, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
+    return launch_dma<128, 128, 2, 2, 64, 2, KIND, BKM>(s, A, lda, B, ldb, M, N, K, epi);
 }
 
 // Pipelined path; the caller has checked K % 32 == 0, N % 8 == 0 and 16-byte alignment of every row.

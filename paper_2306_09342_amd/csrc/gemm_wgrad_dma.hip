@@ -215,28 +215,12 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
     }
 }
 
-int g_wg_stages = 2;   // tuning hook: ring depth (3 and 4 only with REV_TUNE_VARIANTS)
-
 int launch_wgrad_dma(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,
                      int S, int sps, float* out) {
     const int tiles = ((N + WD_BP - 1) / WD_BP) * ((K + WD_BQ - 1) / WD_BQ);
-    static bool attr_set = false;
-    if (!attr_set) {
-        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_dma_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WD_STAGE));
-#ifdef REV_TUNE_VARIANTS
-        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_dma_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, 3 * WD_STAGE));
-        REV_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_dma_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * WD_STAGE));
-#endif
-        attr_set = true;
-    }
-#ifdef REV_TUNE_VARIANTS
-    if (g_wg_stages == 3)
-        hipLaunchKernelGGL(wgrad_dma_kernel<3>, dim3(tiles * S), dim3(256), 3 * WD_STAGE, s, G, ldg, A, lda, M, N, K, sps, out, (int64_t)N * K);
-    else if (g_wg_stages == 4)
-        hipLaunchKernelGGL(wgrad_dma_kernel<4>, dim3(tiles * S), dim3(256), 4 * WD_STAGE, s, G, ldg, A, lda, M, N, K, sps, out, (int64_t)N * K);
-    else
-#endif
-        hipLaunchKernelGGL(wgrad_dma_kernel<2>, dim3(tiles * S), dim3(256), 2 * WD_STAGE, s, G, ldg, A, lda, M, N, K, sps, out, (int64_t)N * K);
+    static LdsLimit lim;
+    if (int rc = lim.ensure(reinterpret_cast<const void*>(wgrad_dma_kernel<2>), 2 * WD_STAGE)) return rc;
+    hipLaunchKernelGGL(wgrad_dma_kernel<2>, dim3(tiles * S), dim3(256), 2 * WD_STAGE, s, G, ldg, A, lda, M, N, K, sps, out, (int64_t)N * K);
     REV_HIP(hipGetLastError());
     return REV_OK;
 }

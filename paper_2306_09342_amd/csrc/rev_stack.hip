@@ -86,7 +86,12 @@ static int check_cfg(const rev_cfg* c) {
     }
     if (dh > 128) { set_error("cfg: head_dim must be <= 128"); return REV_EINVAL; }
     if (c->d_model > 8192 || c->d_mlp > 32768) { set_error("cfg: d_model <= 8192 and d_mlp <= 32768"); return REV_EINVAL; }
-    if ((int64_t)c->batch * c->seq_len >= (1 << 24)) { set_error("cfg: batch*seq_len must be < 2^24"); return REV_EINVAL; }
+    // launch-grid limits: the attention kernels put (sample, head) pairs on the grid's y axis and the plain-ALU
+    // GEMM 64-row strips of tokens; y holds at most 65535
+    if ((int64_t)c->batch * c->seq_len > (int64_t)65535 * 64) {
+        set_error("cfg: batch*seq_len must be <= 4194240"); return REV_EINVAL;
+    }
+    if ((int64_t)c->batch * c->n_heads > 65535) { set_error("cfg: batch*n_heads must be <= 65535"); return REV_EINVAL; }
     if (!(c->ln_eps >= 0.f)) { set_error("cfg: ln_eps must be >= 0"); return REV_EINVAL; }
     return REV_OK;
 }
@@ -185,18 +190,33 @@ static Layout make_layout(const rev_cfg& c, bool compact) {
 // ---------------------------------------------------------------------------------
 // event pool (the only state kept between calls)
 // ---------------------------------------------------------------------------------
+// A two-stream call leases a set of events that no other call holds while it enqueues, so calls issued
+// from several host threads (on their own workspaces and streams) never record or wait on each other's
+// events.  The lease ends when the enqueue returns: a wait that is already enqueued refers to the record
+// that preceded it, so a later call may record the same event again without disturbing it.
 static std::mutex g_ev_mu;
-static std::vector<hipEvent_t> g_events;
-static int get_events(int n, std::vector<hipEvent_t>& out) {
-    std::lock_guard<std::mutex> lk(g_ev_mu);
-    while ((int)g_events.size() < n) {
-        hipEvent_t e;
-        REV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        g_events.push_back(e);
+static std::vector<hipEvent_t> g_ev_free;
+struct EventLease {
+    std::vector<hipEvent_t> ev;
+    int take(int n) {
+        std::lock_guard<std::mutex> lk(g_ev_mu);
+        while ((int)ev.size() < n) {
+            hipEvent_t e;
+            if (!g_ev_free.empty()) {
+                e = g_ev_free.back();
+                g_ev_free.pop_back();
+            } else {
+                REV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            }
+            ev.push_back(e);
+        }
+        return REV_OK;
     }
-    out.assign(g_events.begin(), g_events.begin() + n);
-    return REV_OK;
-}
+    ~EventLease() {
+        std::lock_guard<std::mutex> lk(g_ev_mu);
+        g_ev_free.insert(g_ev_free.end(), ev.begin(), ev.end());
+    }
+};
 
 // ---------------------------------------------------------------------------------
 // the per-block kernel sequences
@@ -407,10 +427,11 @@ struct Runner {
         const bool doR = schedule != 3, doV = schedule != 2;
         // per block: 0 R done, 1 D done, 2 W done, 3 dY2 copy ready (= D start), 4 dh, 5 gY1, 6 dqkv, 7 fc2 wgrad done
         constexpr int EPB = 8;
-        std::vector<hipEvent_t> ev;
+        EventLease lease;
+        std::vector<hipEvent_t>& ev = lease.ev;
         auto E = [&](int i, int k) { return ev[(i - 1) * EPB + k]; };
         if (schedule == 1) {
-            RC(get_events(EPB * N + 1, ev));
+            RC(lease.take(EPB * N + 1));
             REV_HIP(hipEventRecord(ev[EPB * N], sv));            // fork
             REV_HIP(hipStreamWaitEvent(sr, ev[EPB * N], 0));
         } else {

@@ -85,6 +85,24 @@ def test_bad_configs_are_rejected():
     assert B.rev_stack_check_cfg(c) == -1
 
 
+def test_shapes_beyond_the_launch_grid_limits_are_rejected_on_the_host():
+    """(sample, head) pairs and 64-token strips sit on a launch-grid axis that holds 65535 entries: a shape
+    beyond that is refused by the validation, before anything is enqueued, not by a failing launch in mid-pass."""
+    # a window-attention shaped stage: 4096 windows x 24 heads = 98304 (sample, head) pairs
+    c = B.make_cfg(n_blocks=1, d_model=768, n_heads=24, d_mlp=3072, seq_len=49, batch=4096)
+    assert B.rev_stack_check_cfg(c) == -1 and "batch*n_heads" in B.rev_last_error()
+    c = B.make_cfg(n_blocks=1, d_model=768, n_heads=24, d_mlp=3072, seq_len=49, batch=2730)     # 65520 pairs
+    assert B.rev_stack_check_cfg(c) == 0
+    # tokens: 65535 strips of 64
+    c = B.make_cfg(n_blocks=1, d_model=64, n_heads=1, d_mlp=64, seq_len=64, batch=65535)
+    assert B.rev_stack_check_cfg(c) == 0
+    c = B.make_cfg(n_blocks=1, d_model=64, n_heads=1, d_mlp=64, seq_len=65, batch=65535)
+    assert B.rev_stack_check_cfg(c) == -1 and "batch*seq_len" in B.rev_last_error()
+    L = B.lib()
+    fake = ctypes.c_void_p(0x10000)
+    assert L.rev_stack_forward(ctypes.byref(c), fake, fake, fake, fake, fake, fake, 1 << 40, None) == -1
+
+
 def test_null_pointers_and_short_workspace_fail_before_any_gpu_work():
     L = B.lib()
     c = B.make_cfg(**synth.CONFIGS["tiny"])

@@ -204,3 +204,93 @@ def test_pareprop_call_can_be_captured_into_a_graph_and_replayed():
         for k in ref:
             assert torch.equal(out[k], ref[k]), (rep, k)
             assert torch.equal(eager[k], ref[k]) if eager.get(k) is not None else True
+
+
+def test_gelu_tails_bf16_large_preactivations():
+    """fc1 weights and biases scaled so that the MLP pre-activations reach |h| of 10 and more: the bf16 GELU
+    and GELU' epilogues (a polynomial for the normal CDF inside |h| <= 3.8, exactly 0 / 1 beyond) against the
+    oracle's erf form, through the forward map, the inversion and the gradient step."""
+    cfg = dict(n_blocks=2, d_model=128, n_heads=2, d_mlp=512, seq_len=77, batch=3, mode="bf16")
+    flat, _, x, dy1, dy2 = make_case(cfg, seed=11)
+    D, Dm = cfg["d_model"], cfg["d_mlp"]
+    per = synth.params_per_block(D, Dm)
+    rng = np.random.default_rng(5)
+    for blk in range(cfg["n_blocks"]):
+        off = blk * per
+        for tname, shape in synth.block_tensors(D, Dm):
+            n = int(np.prod(shape))
+            if tname == "w_fc1":
+                flat[off:off + n] *= 20.0
+            if tname == "b_fc1":
+                flat[off:off + n] = 2.0 * rng.standard_normal(n)
+            off += n
+    flat = synth.to_bf16_grid(flat)
+    blocks = O.unpack_params(flat, cfg["n_blocks"], D, Dm)
+    H = cfg["n_heads"]
+    # how far the pre-activations of the first block's MLP reach (oracle)
+    y1_0 = x.astype(np.float64) + O.F_forward(x.astype(np.float64), blocks[0], H, 1e-6)[0]
+    h = O.layer_norm(y1_0, blocks[0]["ln2_g"], blocks[0]["ln2_b"], 1e-6)[0] @ blocks[0]["w_fc1"].T + blocks[0]["b_fc1"]
+    frac_tail = float((np.abs(h) > 3.8).mean())
+    print(f"[case] gelu tails: max|h| {np.abs(h).max():.1f}, {100 * frac_tail:.1f} % beyond 3.8", flush=True)
+    assert np.abs(h).max() > 10 and frac_tail > 0.2 and float((h < -3.8).mean()) > 0.1
+    y1, y2 = oracle_forward(cfg, blocks, x, x)
+    y1f, y2f = y1.astype(np.float32), y2.astype(np.float32)
+    ref = O.stack_backward_reversible_chunked(y1f, y2f, blocks, H, dy1, dy2)
+    c = gpu_cfg(cfg)
+    params = to_dev(flat, B.param_dtype(c))
+    gy1, gy2 = B.rev_stack_forward(c, params, to_dev(x), to_dev(x))
+    torch.cuda.synchronize()
+    tol = TOL["bf16"]
+    assert rel_err(gy1.cpu().numpy(), y1) <= tol and rel_err(gy2.cpu().numpy(), y2) <= tol
+    rep = B.rev_stack_backward_reprop(c, params, to_dev(y1f), to_dev(y2f), to_dev(dy1), to_dev(dy2), want_inputs=True)
+    torch.cuda.synchronize()
+    worst = compare_backward(cfg, rep, ref, tol, what="gelu tails")
+    print(f"[ok] gelu tails: worst {max(worst.values()):.3e} at {max(worst, key=worst.get)}", flush=True)
+
+
+def test_two_host_threads_issue_pareprop_calls_concurrently():
+    """Two host threads, each with its own workspace, stream pair, inputs and outputs, enqueue two-stream calls
+    at the same time (each call leases its own events): every result equals, bit for bit, what the same call
+    returns when it is the only one in flight."""
+    import threading
+    cfgs = [dict(SHAPES["ragged_dh64"], mode="bf16"), dict(SHAPES["vit_s_slice"], mode="bf16")]
+    jobs = []
+    for i, cfg in enumerate(cfgs):
+        flat, _, x, dy1, dy2 = make_case(cfg, seed=20 + i)
+        c = gpu_cfg(cfg)
+        params = to_dev(flat, B.param_dtype(c))
+        X, dY1, dY2 = to_dev(x), to_dev(dy1), to_dev(dy2)
+        Y1, Y2 = B.rev_stack_forward(c, params, X, X)
+        torch.cuda.synchronize()
+        ws = B.alloc_workspace(c)
+        sg, sr = torch.cuda.Stream(), torch.cuda.Stream()
+        alone = B.rev_stack_backward_pareprop(c, params, Y1, Y2, dY1, dY2, sr, workspace=ws, stream_grad=sg)
+        torch.cuda.synchronize()
+        jobs.append(dict(c=c, params=params, Y1=Y1, Y2=Y2, dY1=dY1, dY2=dY2, ws=ws, sg=sg, sr=sr,
+                         alone={k: v.clone() for k, v in alone.items() if v is not None}, results=[], err=None))
+    start = threading.Barrier(len(jobs))
+
+    def worker(j):
+        try:
+            torch.cuda.set_device(0)
+            start.wait()
+            for _ in range(6):
+                out = B.rev_stack_backward_pareprop(j["c"], j["params"], j["Y1"], j["Y2"], j["dY1"], j["dY2"], j["sr"],
+                                                    workspace=j["ws"], stream_grad=j["sg"])
+                j["sg"].synchronize()
+                j["results"].append({k: v.clone() for k, v in out.items() if v is not None})
+        except Exception as e:          # surfaces in the main thread
+            j["err"] = e
+
+    threads = [threading.Thread(target=worker, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for j in jobs:
+        assert j["err"] is None, j["err"]
+        assert len(j["results"]) == 6
+        for r in j["results"]:
+            for k, v in j["alone"].items():
+                assert torch.equal(r[k], v), k
