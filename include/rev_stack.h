@@ -170,6 +170,28 @@ int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params,
                                 void* workspace, int64_t workspace_bytes,
                                 void* stream_grad, void* stream_recompute);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): rev_stack_backward_reprop
+ * without the workspace argument.  The workspace is a buffer of
+ * REV_STATIC_WORKSPACE_BYTES that is part of the library's device image, so each
+ * GPU the library runs on holds it from load until the process ends; the call
+ * allocates nothing, on the device or through any library (it creates no events
+ * either), and frees nothing.  Same arguments, results (bit for bit), ordering
+ * and errors as rev_stack_backward_reprop, plus: REV_EWORKSPACE, before anything
+ * is enqueued, if rev_stack_workspace_bytes_reprop(cfg) exceeds
+ * REV_STATIC_WORKSPACE_BYTES (the message says what the shape needs).  All calls
+ * on one GPU share the one buffer, which keeps the previous call's contents
+ * (every region is written before it is read, nothing has to start at zero):
+ * two such calls that overlap in time on one GPU race, also from different
+ * streams or host threads -- order them on one stream or with events. */
+#define REV_STATIC_WORKSPACE_BYTES (64 * 1024 * 1024)
+int rev_stack_backward_reprop_static(const rev_cfg* cfg, const void* params,
+                                     const float* Y1, const float* Y2,
+                                     const float* dY1, const float* dY2,
+                                     float* dX1, float* dX2,
+                                     float* X1_out, float* X2_out, float* dparams,
+                                     void* stream);
+
 /* Optimizer update of a training step: AdamW, the optimizer of the paper's
  * throughput experiments (Sec. 4, experimental setup; the paper gives neither
  * formula nor hyper-parameters, so this is the published update with decoupled

@@ -23,6 +23,7 @@ EXPORTS = (
     "rev_stack_check_cfg", "rev_stack_param_count", "rev_stack_param_offset", "rev_stack_workspace_bytes",
     "rev_stack_workspace_bytes_reprop", "rev_stack_slot_bytes",
     "rev_stack_forward", "rev_stack_backward_reprop", "rev_stack_backward_pareprop", "rev_stack_backward_chain",
+    "rev_stack_backward_reprop_static",
     "rev_stack_forward_masked", "rev_stack_backward_reprop_masked", "rev_stack_backward_pareprop_masked",
     "rev_adamw_step", "rev_sgd_step",
     "rev_merge_check_cfg", "rev_merge_param_count", "rev_merge_workspace_bytes", "rev_merge_forward", "rev_merge_backward",
@@ -73,6 +74,8 @@ def lib():
         bw = [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64]
         L.rev_stack_backward_reprop.argtypes = bw + [vp]
         L.rev_stack_backward_reprop.restype = ctypes.c_int
+        L.rev_stack_backward_reprop_static.argtypes = bw[:-2] + [vp]
+        L.rev_stack_backward_reprop_static.restype = ctypes.c_int
         L.rev_stack_backward_pareprop.argtypes = bw + [vp, vp]
         L.rev_stack_backward_pareprop.restype = ctypes.c_int
         L.rev_stack_backward_chain.argtypes = bw + [vp, i32]
@@ -224,6 +227,23 @@ def rev_stack_backward_reprop(cfg, params, Y1, Y2, dY1, dY2, workspace=None, str
     args, res = _backward_args(cfg, params, Y1, Y2, dY1, dY2, workspace, want_inputs, out)
     _check(lib().rev_stack_backward_reprop(*args, _stream_handle(stream)))
     return res
+
+
+STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024      # REV_STATIC_WORKSPACE_BYTES of the header
+
+
+def rev_stack_backward_reprop_static(cfg, params, Y1, Y2, dY1, dY2, out, stream=None):
+    """The sequential schedule in the library's built-in workspace: nothing is allocated, here or in the
+    library, so `out` must hold dX1, dX2 and dparams (and X1, X2 if the reconstructed inputs are wanted)."""
+    shape = (cfg.batch, cfg.seq_len, cfg.d_model)
+    _want(params, param_dtype(cfg), (rev_stack_param_count(cfg),))
+    for t in (Y1, Y2, dY1, dY2, out["dX1"], out["dX2"]):
+        _want(t, torch.float32, shape)
+    _want(out["dparams"], torch.float32, (params.numel(),))
+    _check(lib().rev_stack_backward_reprop_static(
+        ctypes.byref(cfg), _ptr(params), _ptr(Y1), _ptr(Y2), _ptr(dY1), _ptr(dY2), _ptr(out["dX1"]), _ptr(out["dX2"]),
+        _ptr(out.get("X1")), _ptr(out.get("X2")), _ptr(out["dparams"]), _stream_handle(stream)))
+    return out
 
 
 def rev_stack_backward_pareprop(cfg, params, Y1, Y2, dY1, dY2, stream_recompute, workspace=None, stream_grad=None,

@@ -557,6 +557,33 @@ static int backward_entry(int schedule, const rev_cfg* cfg, const void* params, 
     return r.backward(schedule, Y1, Y2, dY1, dY2, dX1, dX2, X1o, X2o, (hipStream_t)sv, (hipStream_t)sr);
 }
 
+// ---------------------------------------------------------------------------------
+// file-scope scratch of the allocation-free entry point
+// ---------------------------------------------------------------------------------
+// The workspace of rev_stack_backward_reprop_static: every GPU the library runs on holds its own copy of this
+// array from the moment the code object is loaded until the process ends.  In host code the name `scratch` is only
+// a stand-in for the symbol: the device address is looked up once per device and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[REV_STATIC_WORKSPACE_BYTES];
+
+static std::mutex g_scratch_mu;
+static std::vector<void*> g_scratch_ptr;     // indexed by device ordinal; nullptr = not looked up yet
+
+// device address of `scratch` on the current device
+static int scratch_address(void** out) {
+    int dev = 0;
+    REV_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if ((int)g_scratch_ptr.size() <= dev) g_scratch_ptr.resize(dev + 1, nullptr);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        REV_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255) != 0) { set_error("static workspace: bad symbol address"); return REV_EHIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return REV_OK;
+}
+
 }  // namespace rev
 
 using namespace rev;
@@ -632,6 +659,23 @@ int rev_stack_backward_reprop(const rev_cfg* cfg, const void* params, const floa
                               const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1_out, float* X2_out,
                               float* dparams, void* ws, int64_t ws_bytes, void* stream) {
     return backward_entry(0, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws, ws_bytes, stream, stream);
+}
+
+int rev_stack_backward_reprop_static(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
+                                     const float* dY1, const float* dY2, float* dX1, float* dX2, float* X1_out,
+                                     float* X2_out, float* dparams, void* stream) {
+    RC(check_cfg(cfg));
+    const int64_t need = make_layout(*cfg, true).total;
+    if (need > (int64_t)REV_STATIC_WORKSPACE_BYTES) {
+        set_error("static workspace too small for this shape: the sequential schedule needs " + std::to_string(need) +
+                  " bytes, the built-in buffer holds " + std::to_string((int64_t)REV_STATIC_WORKSPACE_BYTES) +
+                  "; use rev_stack_backward_reprop with a caller-provided workspace");
+        return REV_EWORKSPACE;
+    }
+    void* ws = nullptr;
+    RC(scratch_address(&ws));
+    return backward_entry(0, cfg, params, Y1, Y2, dY1, dY2, dX1, dX2, X1_out, X2_out, dparams, ws,
+                          (int64_t)REV_STATIC_WORKSPACE_BYTES, stream, stream);
 }
 
 int rev_stack_backward_pareprop(const rev_cfg* cfg, const void* params, const float* Y1, const float* Y2,
