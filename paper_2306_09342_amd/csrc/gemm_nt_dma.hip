@@ -26,98 +26,10 @@
 // has the device to itself picks when 128-row tiles would leave a short, ragged
 // last round of workgroups; and 64x128 with two wavefronts of 64x64 for launches
 // too small to give every second CU a 128-row tile.
-#include "mfma.h"
+#include "gemm_epilogue.h"
 #include <type_traits>
 
 namespace rev {
-
-// Normal CDF for the bf16 GELU epilogues: Phi(x) = 1/2 + x * P(x^2) on |x| <= 3.8 with a degree-6 minimax-fitted P
-// (absolute error < 6.5e-5 there; plain FMAs, no transcendental), and exactly 0 / 1 beyond, so that gelu(x) is exactly
-// 0 for x < -3.8 (the true value is below 2.8e-4 in magnitude and shrinking) and exactly x for x > 3.8.  The bound is an
-// absolute one: relative to the small negative-tail values of gelu it is not small (4.6 % at x = -3).
-// The density, needed by the derivative only, is one exp.
-__device__ __forceinline__ float gelu_cdf(float x) {
-    const float xc = fminf(fmaxf(x, -3.8f), 3.8f);
-    const float u = xc * xc;
-    float p = 3.665773107e-08f;
-    p = p * u - 2.272460051e-06f;
-    p = p * u + 6.068476796e-05f;
-    p = p * u - 9.315473144e-04f;
-    p = p * u + 9.316634387e-03f;
-    p = p * u - 6.571978331e-02f;
-    p = p * u + 3.986767530e-01f;
-    float r = 0.5f + xc * p;
-    r = x < -3.8f ? 0.f : r;
-    r = x > 3.8f ? 1.f : r;
-    return r;
-}
-__device__ __forceinline__ float gelu_pdf(float x) { return 0.39894228040143268f * __expf(-0.5f * x * x); }
-
-typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ f32x4_t ld_bf16x4(const void* p) {
-    const u32x2_t u = *reinterpret_cast<const u32x2_t*>(p);
-    f32x4_t r;
-    r[0] = __uint_as_float(u[0] << 16);
-    r[1] = __uint_as_float(u[0] & 0xFFFF0000u);
-    r[2] = __uint_as_float(u[1] << 16);
-    r[3] = __uint_as_float(u[1] & 0xFFFF0000u);
-    return r;
-}
-__device__ __forceinline__ void st_bf16x4(void* p, f32x4_t v) {
-    bf16x4_t b;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) b[e] = (__bf16)v[e];
-    *reinterpret_cast<bf16x4_t*>(p) = b;
-}
-
-// The epilogue operand of 4 consecutive output columns n..n+3 of row m (residual stream or saved
-// pre-activation), loaded ahead of the arithmetic so that all loads of a panel are in flight together.
-template <int KIND>
-__device__ __forceinline__ f32x4_t epi_load4(const Epi& e, int m, int n) {
-    const int64_t idx = (int64_t)m * e.ldo + n;
-    if (KIND == EPI_RESIDUAL) return *reinterpret_cast<const f32x4_t*>(e.res + idx);
-    if (KIND == EPI_GELU_BWD) {
-        // the 4 bf16 values stay packed (2 registers) until epi_store4 unpacks them
-        const u32x2_t u = *reinterpret_cast<const u32x2_t*>(reinterpret_cast<const bf16*>(e.aux) + idx);
-        return f32x4_t{__uint_as_float(u[0]), __uint_as_float(u[1]), 0.f, 0.f};
-    }
-    return f32x4_t{0.f, 0.f, 0.f, 0.f};
-}
-
-// 4 consecutive output columns n..n+3 of row m; `opnd` is what epi_load4 returned for them
-// (returns the float32 values behind the stored output, for the fused column sums)
-template <int KIND>
-__device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_t acc, f32x4_t bv, f32x4_t opnd) {
-    const int64_t idx = (int64_t)m * e.ldo + n;
-    if (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU || KIND == EPI_RESIDUAL) acc += bv;
-    if (KIND == EPI_BIAS) {
-        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
-    } else if (KIND == EPI_BIAS_GELU) {
-        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
-        f32x4_t a;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) a[k] = acc[k] * gelu_cdf(acc[k]);
-        st_bf16x4(reinterpret_cast<bf16*>(e.out2) + idx, a);
-    } else if (KIND == EPI_RESIDUAL) {
-        *reinterpret_cast<f32x4_t*>(e.outf + idx) = opnd + e.sign * acc;
-    } else if (KIND == EPI_GELU_BWD) {
-        const unsigned u0 = __float_as_uint(opnd[0]), u1 = __float_as_uint(opnd[1]);
-        const f32x4_t h = {__uint_as_float(u0 << 16), __uint_as_float(u0 & 0xFFFF0000u),
-                           __uint_as_float(u1 << 16), __uint_as_float(u1 & 0xFFFF0000u)};
-        f32x4_t o;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) o[k] = acc[k] * (gelu_cdf(h[k]) + h[k] * gelu_pdf(h[k]));
-        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, o);
-        return o;
-    } else if (KIND == EPI_PLAIN) {
-        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
-    } else {
-        *reinterpret_cast<f32x4_t*>(e.outf + idx) = acc;
-    }
-    return acc;
-}
 
 template <int BM, int BN, int WM, int WN, int BK, int NS, int KIND, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* __restrict__ A, int64_t lda,
@@ -206,7 +118,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     // product groups of the current one, so the matrix cores start right after the barrier.
     constexpr bool SPREAD = (NW == 4 && TM * TN >= 16 && NS == 2 && LPW % (BK / 16) == 0);
     // 64x64 per wavefront (four wavefronts, the default 128x128 tile) or 160x64 (two wavefronts, the tall tile)
-    constexpr bool HANDPLACED_SHAPE = (((TM == 2 && (NW == 4 || NW == 2)) || (TM == 5 && NW == 2)) && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
+    constexpr bool HANDPLACED_SHAPE = (((TM == 2 && (NW == 4 || NW == 2)) || (TM == 5 && NW == 2) || (TM == 4 && NW == 8)) && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
 
     // Epilogue geometry (a wavefront's 32-row panels leave through LDS in full rows) and, for the
     // epilogues that read a second operand (residual stream, saved pre-activation), that operand:
@@ -220,7 +132,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int n = n0 + wn * CW + 4 * c4;
     // (float32 residual rows cost 4 registers each: only the first panel's are held across the main
     // loop, the second panel's are requested when the epilogue starts)
-    constexpr int PRE = !HANDPLACED_SHAPE ? 0 : (KIND == EPI_GELU_BWD ? (TM > 2 ? 2 : TM) : (KIND == EPI_RESIDUAL ? 1 : 0));
+    constexpr int PRE = (!HANDPLACED_SHAPE || TM == 4) ? 0 : (KIND == EPI_GELU_BWD ? (TM > 2 ? 2 : TM) : (KIND == EPI_RESIDUAL ? 1 : 0));
     f32x4_t opnd_pre[TM][NP];
     if (PRE > 0 && n < N) {
 #pragma unroll
@@ -286,15 +198,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
                 dma16_sbase((NW * t) < IA ? ak : bk, voff[t], sbase + dst[t]);
         };
         auto stage_body = [&](auto stage_tag, auto next_tag, int kt) {
-            constexpr int SOFF = decltype(stage_tag)::value * STAGE;
+            // the stage offset rides in the instruction's 16-bit offset field where the whole ring fits it;
+            // larger rings add it to the address registers
+            constexpr bool BIG_RING = NS * STAGE > 65536;
+            constexpr int SOFF = BIG_RING ? 0 : decltype(stage_tag)::value * STAGE;
+            constexpr unsigned SADD = BIG_RING ? decltype(stage_tag)::value * STAGE : 0;
             constexpr bool has_next = decltype(next_tag)::value;
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __builtin_amdgcn_s_barrier();
             u32x4_t a[4][TM], b[4][2];
             auto read_group = [&](auto kk_tag) {
                 constexpr int kk = decltype(kk_tag)::value;
-                a[kk][0] = lds_read_b128(a_addr[kk], SOFF);
-                a[kk][1] = lds_read_b128(a_addr[kk], SOFF + 32 * ROWB);
+                a[kk][0] = lds_read_b128(a_addr[kk] + SADD, SOFF);
+                a[kk][1] = lds_read_b128(a_addr[kk] + SADD, SOFF + 32 * ROWB);
+                if constexpr (TM == 4) {
+                    a[kk][2] = lds_read_b128(a_addr[kk] + SADD, SOFF + 64 * ROWB);
+                    a[kk][3] = lds_read_b128(a_addr[kk] + SADD, SOFF + 96 * ROWB);
+                }
                 if constexpr (TM == 5) {
                     a[kk][2] = lds_read_b128(a_addr[kk], SOFF + 64 * ROWB);
                     a[kk][3] = lds_read_b128(a_addr[kk], SOFF + 96 * ROWB);
@@ -306,8 +226,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
                         b[kk][j] = join64(lds_read_tr16_b64(bt_addr[j], SOFF + kk * 16 * 256),
                                           lds_read_tr16_b64(bt_addr[j], SOFF + kk * 16 * 256 + 4 * 256));
                 } else {
-                    b[kk][0] = lds_read_b128(b_addr[kk], SOFF);
-                    b[kk][1] = lds_read_b128(b_addr[kk], SOFF + 32 * ROWB);
+                    b[kk][0] = lds_read_b128(b_addr[kk] + SADD, SOFF);
+                    b[kk][1] = lds_read_b128(b_addr[kk] + SADD, SOFF + 32 * ROWB);
                 }
             };
             auto products = [&](int kk) {
@@ -320,7 +240,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             // waits until at most N younger LDS reads are outstanding; carries step kk's fragments
             auto wait_group = [&](auto n_tag, int kk) {
                 constexpr int N = decltype(n_tag)::value;
-                if constexpr (TM == 5) lds_wait7<N>(a[kk][0], a[kk][1], a[kk][2], a[kk][3], a[kk][4], b[kk][0], b[kk][1]);
+                if constexpr (TM == 4) lds_wait6<N>(a[kk][0], a[kk][1], a[kk][2], a[kk][3], b[kk][0], b[kk][1]);
+                else if constexpr (TM == 5) lds_wait7<N>(a[kk][0], a[kk][1], a[kk][2], a[kk][3], a[kk][4], b[kk][0], b[kk][1]);
                 else lds_wait4<N>(a[kk][0], a[kk][1], b[kk][0], b[kk][1]);
             };
             using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
@@ -331,10 +252,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             // its own operands (the reads of the step after it stay in flight)
             read_group(I0{}); read_group(I1{});
             if (has_next) issue(kt + 1, 1 - decltype(stage_tag)::value);
-            wait_group(NRPK{}, 0); products(0);
-            read_group(I2{});
-            wait_group(NRPK{}, 1); products(1);
-            read_group(I3{});
+            wait_group(NRPK{}, 0); read_group(I2{}); products(0);
+            wait_group(NRPK{}, 1); read_group(I3{}); products(1);
             wait_group(NRPK{}, 2); products(2);
             wait_group(N0{}, 3);   products(3);
         };
