@@ -141,7 +141,7 @@ def bench_hierarchy(args, hier, B, synth, torch, np):
     side = torch.cuda.Stream()
     stages = []
     merges = []
-    mcfgs = synth.merge_cfgs(hier)
+    mcfgs = synth.merge_cfgs(hier, fusion=args.fusion)
     X1 = X2 = None
     for si, cfg in enumerate(hier["stages"]):
         c = B.make_cfg(**cfg)
@@ -249,7 +249,8 @@ def bench_hierarchy(args, hier, B, synth, torch, np):
         "ms_per_step": wall_p / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {len(stages)} stages of window-attention shaped reversible stacks joined by "
-                               f"{len(merges)} stage transitions (stream averaging + patch merging), {images} images of 224x224",
+                               f"{len(merges)} stage transitions (stream fusion by {'a small MLP' if args.fusion == 'mlp' else 'averaging'} "
+                               f"+ patch merging), {images} images of 224x224",
                    "schedule": "pareprop (2 HIP streams)"},
         "pareprop": {"images_per_s": value, "ms_median": float(np.median(ms_p)), "ms_std": float(ms_p.std())},
         "reprop": {"images_per_s": images * args.steps / wall_r, "ms_median": float(np.median(ms_r)),
@@ -314,6 +315,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["all", "reprop", "pareprop"], default="all",
                     help="restrict the run to one schedule (for profiler runs); the JSON line then lacks the other")
+    ap.add_argument("--fusion", choices=["average", "mlp"], default="average",
+                    help="hierarchical workloads: how a stage transition fuses the two streams (Sec. 3.4)")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short both-schedules runs on the other workloads")
     ap.add_argument("--cpu-samples", type=int, default=0, help="samples the oracle is timed on (0 = auto)")

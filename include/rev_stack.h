@@ -269,8 +269,11 @@ int rev_stack_backward_chain(const rev_cfg* cfg, const void* params,
  * Between two stages of its hierarchical (window-attention) model the paper
  * places a block that first fuses the two residual streams (by averaging, or
  * by a small MLP) and then applies the usual patch merging (Sec. 3.4 and
- * panel (b) of the architecture figure).  The reading built here: fusion by
- * averaging; patch merging = concatenate every 2x2 neighbourhood of the token
+ * panel (b) of the architecture figure).  The readings built here: fusion by
+ * averaging, z0 = (X1 + X2) / 2 (cfg.fusion = REV_FUSION_AVERAGE), or by a small
+ * MLP on the concatenated streams, z0 = gelu([X1 | X2] Wa^T + ba) Wb^T + bb with
+ * one hidden layer as wide as a stream (REV_FUSION_MLP; the GELU of the blocks);
+ * patch merging = concatenate every 2x2 neighbourhood of the token
  * grid along the feature axis (C -> 4C, neighbour (dy, dx) at feature block
  * 2*dy + dx), LayerNorm over the 4C features, bias-free linear map 4C -> 2C;
  * both streams of the next stage start from the result, so the backward pass
@@ -285,12 +288,16 @@ int rev_stack_backward_chain(const rev_cfg* cfg, const void* params,
  * has (grid_h/2) x (grid_w/2) tokens per image in the same order.
  *
  * Packed parameters (element type as in rev_cfg.mode): ln_gamma[4C],
- * ln_beta[4C], W[2C, 4C] row-major.  dparams: same layout, float32,
+ * ln_beta[4C], W[2C, 4C] row-major, and with REV_FUSION_MLP behind them
+ * Wa[C, 2C], ba[C], Wb[C, C], bb[C].  dparams: same layout, float32,
  * overwritten.  X1, X2, dX1, dX2: [batch*grid_h*grid_w, C] float32.  out, dOutA,
  * dOutB: [batch*grid_h*grid_w/4, 2C] float32.  All device pointers, 16-byte
  * aligned; the workspace 256-byte aligned and at least
  * rev_merge_workspace_bytes() long.  Calls enqueue on `stream` and return;
  * nothing is allocated.  Errors as for the rev_stack_* calls. */
+#define REV_FUSION_AVERAGE 0
+#define REV_FUSION_MLP     1
+
 typedef struct rev_merge_cfg {
     int32_t batch;      /* images                                              */
     int32_t grid_h;     /* token grid of the incoming stage; both sides must   */
@@ -299,10 +306,11 @@ typedef struct rev_merge_cfg {
     int32_t d_in;       /* width C of the incoming stage (multiple of 8, <= 2048) */
     int32_t mode;       /* REV_MODE_FP32 or REV_MODE_BF16                      */
     float   ln_eps;
+    int32_t fusion;     /* REV_FUSION_AVERAGE or REV_FUSION_MLP                */
 } rev_merge_cfg;
 
 int     rev_merge_check_cfg(const rev_merge_cfg* cfg);
-int64_t rev_merge_param_count(const rev_merge_cfg* cfg);      /* 8C + 8C^2 */
+int64_t rev_merge_param_count(const rev_merge_cfg* cfg);      /* 8C + 8C^2 (+ 3C^2 + 2C with the MLP fusion) */
 int64_t rev_merge_workspace_bytes(const rev_merge_cfg* cfg);
 int rev_merge_forward(const rev_merge_cfg* cfg, const void* params,
                       const float* X1, const float* X2, float* out,

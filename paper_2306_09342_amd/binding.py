@@ -41,7 +41,7 @@ class RevCfg(ctypes.Structure):
 class RevMergeCfg(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
                 ("window", ctypes.c_int32), ("d_in", ctypes.c_int32), ("mode", ctypes.c_int32),
-                ("ln_eps", ctypes.c_float)]
+                ("ln_eps", ctypes.c_float), ("fusion", ctypes.c_int32)]
 
 
 class RevError(RuntimeError):
@@ -323,9 +323,13 @@ def rev_sgd_step(master, grad, lr, params_bf16=None, stream=None):
     _check(lib().rev_sgd_step(master.numel(), _ptr(master), _ptr(params_bf16), _ptr(grad), lr, _stream_handle(stream)))
 
 
-def make_merge_cfg(batch, grid_h, grid_w, window, d_in, mode="bf16", ln_eps=1e-5) -> RevMergeCfg:
+FUSIONS = {"average": 0, "mlp": 1}
+
+
+def make_merge_cfg(batch, grid_h, grid_w, window, d_in, mode="bf16", ln_eps=1e-5, fusion="average") -> RevMergeCfg:
     m = MODES[mode] if isinstance(mode, str) else int(mode)
-    return RevMergeCfg(batch, grid_h, grid_w, window, d_in, m, ln_eps)
+    f = FUSIONS[fusion] if isinstance(fusion, str) else int(fusion)
+    return RevMergeCfg(batch, grid_h, grid_w, window, d_in, m, ln_eps, f)
 
 
 def rev_merge_check_cfg(cfg: RevMergeCfg) -> int:

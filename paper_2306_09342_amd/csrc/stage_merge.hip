@@ -1,12 +1,15 @@
 // Stage transition of a hierarchical reversible model (paper Sec. 3.4, "downsample block"): the two
-// residual streams are fused by averaging, every 2x2 neighbourhood of the token grid is concatenated
-// (C -> 4C features), normalised by a LayerNorm and reduced by a bias-free linear map to 2C.  The block
-// is not reversible: its backward pass gets the block's inputs from the caller.
+// residual streams are fused (by averaging, or by a small MLP), every 2x2 neighbourhood of the token grid
+// is concatenated (C -> 4C features), normalised by a LayerNorm and reduced by a bias-free linear map to 2C.
+// The block is not reversible: its backward pass gets the block's inputs from the caller.
 //
-// Forward:   z[o, q*C + c] = (X1[src(o,q), c] + X2[src(o,q), c]) / 2,  q = 2*dy + dx
-//            n = LN(z),  out = n * W^T
+// Forward:   z0 = (X1 + X2) / 2                                     (fusion by averaging), or
+//            z0 = gelu([X1 | X2] * Wa^T + ba) * Wb^T + bb           (fusion by a small MLP, Wa [C, 2C], Wb [C, C])
+//            z[o, q*C + c] = z0[src(o,q), c],  q = 2*dy + dx;   n = LN(z),  out = n * W^T
 // Backward:  dout = dOutA + dOutB (both streams of the next stage start from `out`)
-//            dW = dout^T * n,  dn = dout * W,  dz = LNbwd(dn),  dX1[src] = dX2[src] = dz / 2
+//            dW = dout^T * n,  dn = dout * W,  dz = LNbwd(dn),  dz0[src] = dz,
+//            averaging: dX1 = dX2 = dz0 / 2;   MLP: the two linear maps and the GELU backwards, recomputed
+//            from X1, X2 (the block keeps nothing between its two calls)
 //
 // Tokens are stored window by window (the windows are the attention sequences of the stages), on
 // both sides of the block.  The gather, the average and the LayerNorm are one kernel (a wavefront
@@ -49,8 +52,10 @@ __device__ __forceinline__ void merge_sources(const MergeGeom& g, int o, int src
 }
 
 // ---- gather + average + LayerNorm ---------------------------------------------------------------
-template <typename TA, typename TP, int MAXJ>
+// FUSED: the fused map z0 (activation type) is given; otherwise it is the average of X1 and X2, taken on the fly.
+template <typename TA, typename TP, int MAXJ, bool FUSED>
 __global__ __launch_bounds__(256) void merge_ln_fwd_kernel(const float* __restrict__ X1, const float* __restrict__ X2,
+                                                           const TA* __restrict__ Z0,
                                                            const TP* __restrict__ gam, const TP* __restrict__ bet, float eps,
                                                            TA* __restrict__ n, float* __restrict__ stats, MergeGeom g, int Mo) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -66,8 +71,12 @@ __global__ __launch_bounds__(256) void merge_ln_fwd_kernel(const float* __restri
         if (c < nch) {
             const int q = (4 * c) / C, col = 4 * c - q * C;
             const int64_t off = (int64_t)src[q] * C + col;
-            const f4 a = load4(X1 + off), b = load4(X2 + off);
-            v[j] = {0.5f * (a.x + b.x), 0.5f * (a.y + b.y), 0.5f * (a.z + b.z), 0.5f * (a.w + b.w)};
+            if (FUSED) {
+                v[j] = load4(Z0 + off);
+            } else {
+                const f4 a = load4(X1 + off), b = load4(X2 + off);
+                v[j] = {0.5f * (a.x + b.x), 0.5f * (a.y + b.y), 0.5f * (a.z + b.z), 0.5f * (a.w + b.w)};
+            }
         }
     }
     float s = 0.f;
@@ -106,11 +115,15 @@ __global__ __launch_bounds__(256) void merge_ln_fwd_kernel(const float* __restri
 // ---- LayerNorm backward on the re-gathered row + scatter of the halves to both streams -------------
 // Each block walks rows_per_block consecutive output rows (4 wavefronts, one row each at a time) and
 // writes one partial row [d gamma | d beta], its wavefronts folded in wavefront order.
-template <typename TA, typename TP, int MAXJ>
+// FUSED: rows are re-gathered from the fused map z0 and their cotangent goes, whole, to dZ0 (activation type);
+// otherwise from the average of X1 and X2, and half of it goes to each of dX1, dX2.
+template <typename TA, typename TP, int MAXJ, bool FUSED>
 __global__ __launch_bounds__(256) void merge_ln_bwd_kernel(const TA* __restrict__ dn, const float* __restrict__ X1,
-                                                           const float* __restrict__ X2, const float* __restrict__ stats,
+                                                           const float* __restrict__ X2, const TA* __restrict__ Z0,
+                                                           const float* __restrict__ stats,
                                                            const TP* __restrict__ gam, float* __restrict__ dX1,
-                                                           float* __restrict__ dX2, float* __restrict__ partial,
+                                                           float* __restrict__ dX2, TA* __restrict__ dZ0,
+                                                           float* __restrict__ partial,
                                                            MergeGeom g, int Mo, int rows_per_block) {
     extern __shared__ float lds[];                   // [2 * 4C]
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -137,9 +150,15 @@ __global__ __launch_bounds__(256) void merge_ln_bwd_kernel(const TA* __restrict_
             if (c < nch) {
                 const int q = (4 * c) / C, col = 4 * c - q * C;
                 const int64_t off = (int64_t)src[q] * C + col;
-                const f4 a = load4(X1 + off), b = load4(X2 + off), d = load4(dn + (int64_t)o * D4 + 4 * c);
-                xh[j] = {(0.5f * (a.x + b.x) - mean) * rstd, (0.5f * (a.y + b.y) - mean) * rstd,
-                         (0.5f * (a.z + b.z) - mean) * rstd, (0.5f * (a.w + b.w) - mean) * rstd};
+                const f4 d = load4(dn + (int64_t)o * D4 + 4 * c);
+                f4 zz;
+                if (FUSED) {
+                    zz = load4(Z0 + off);
+                } else {
+                    const f4 a = load4(X1 + off), b = load4(X2 + off);
+                    zz = {0.5f * (a.x + b.x), 0.5f * (a.y + b.y), 0.5f * (a.z + b.z), 0.5f * (a.w + b.w)};
+                }
+                xh[j] = {(zz.x - mean) * rstd, (zz.y - mean) * rstd, (zz.z - mean) * rstd, (zz.w - mean) * rstd};
                 ab[j].x += d.x; ab[j].y += d.y; ab[j].z += d.z; ab[j].w += d.w;
                 ag[j].x += d.x * xh[j].x; ag[j].y += d.y * xh[j].y; ag[j].z += d.z * xh[j].z; ag[j].w += d.w * xh[j].w;
                 dh[j] = {d.x * gg[j].x, d.y * gg[j].y, d.z * gg[j].z, d.w * gg[j].w};
@@ -149,7 +168,7 @@ __global__ __launch_bounds__(256) void merge_ln_bwd_kernel(const TA* __restrict_
         }
         c1 = wave_sum(c1) / (float)D4;
         c2 = wave_sum(c2) / (float)D4;
-        const float hr = 0.5f * rstd;
+        const float hr = FUSED ? rstd : 0.5f * rstd;
 #pragma unroll
         for (int j = 0; j < MAXJ; ++j) {
             const int c = lane + 64 * j;
@@ -161,8 +180,12 @@ __global__ __launch_bounds__(256) void merge_ln_bwd_kernel(const TA* __restrict_
                 r.y = hr * (dh[j].y - c1 - xh[j].y * c2);
                 r.z = hr * (dh[j].z - c1 - xh[j].z * c2);
                 r.w = hr * (dh[j].w - c1 - xh[j].w * c2);
-                store4(dX1 + off, r);
-                store4(dX2 + off, r);
+                if (FUSED) {
+                    store4(dZ0 + off, r);
+                } else {
+                    store4(dX1 + off, r);
+                    store4(dX2 + off, r);
+                }
             }
         }
     }
@@ -202,6 +225,18 @@ __global__ __launch_bounds__(256) void add2_kernel(const float* __restrict__ a, 
     }
 }
 
+// cat[m, 0:C] = X1[m, :], cat[m, C:2C] = X2[m, :], converted to the activation type
+template <typename TA>
+__global__ __launch_bounds__(256) void concat2_kernel(const float* __restrict__ X1, const float* __restrict__ X2,
+                                                      TA* __restrict__ cat, int64_t M, int C4) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;       // one 4-element chunk of one source row
+    if (i >= M * C4) return;
+    const int64_t m = i / C4;
+    const int c = (int)(i - m * C4);
+    store4(cat + (m * 2 * C4 + c) * 4, load4(X1 + i * 4));
+    store4(cat + (m * 2 * C4 + C4 + c) * 4, load4(X2 + i * 4));
+}
+
 // rows per block of the backward kernel: about 1024 blocks, at least 8 and at most 64 rows each
 static int merge_rows_per_block(int Mo) {
     int rpb = ((Mo + 1023) / 1024 + 3) / 4 * 4;
@@ -216,9 +251,13 @@ int64_t wgrad_partial_elems(int M, int N, int K);   // gemm_mfma.hip
 struct MergeLayout {
     int64_t n, stats, dob, dn, part_ln, part_wg, total;
     int64_t part_wg_elems;
+    // fusion by a small MLP only: [X1 | X2], hidden pre-activation and activation, fused map, its cotangent, the
+    // hidden cotangent (all [M, .] in the activation type), and the partial sums of the four parameter gradients
+    int64_t cat, h, a, z0, dz0, dh, part_col[2], part_fw[2];
+    int64_t part_fw_elems[2];
 };
 static MergeLayout merge_layout(const rev_merge_cfg& c) {
-    MergeLayout L;
+    MergeLayout L = {};
     const int64_t es = (c.mode == REV_MODE_BF16) ? 2 : 4;
     const int64_t Mo = (int64_t)c.batch * (c.grid_h / 2) * (c.grid_w / 2), C = c.d_in;
     int64_t pos = 0;
@@ -231,6 +270,21 @@ static MergeLayout merge_layout(const rev_merge_cfg& c) {
     L.part_ln = take(((Mo + rpb - 1) / rpb) * 8 * C * 4);
     L.part_wg_elems = (c.mode == REV_MODE_BF16) ? wgrad_partial_elems((int)Mo, (int)(2 * C), (int)(4 * C)) : 0;
     L.part_wg = take(L.part_wg_elems * 4);
+    if (c.fusion == REV_FUSION_MLP) {
+        const int64_t M = 4 * Mo;
+        L.cat = take(M * 2 * C * es);
+        L.h = take(M * C * es);
+        L.a = take(M * C * es);
+        L.z0 = take(M * C * es);
+        L.dz0 = take(M * C * es);
+        L.dh = take(M * C * es);
+        L.part_col[0] = take(colsum_partial_elems((int)M, (int)C) * 4);
+        L.part_col[1] = take(colsum_partial_elems((int)M, (int)C) * 4);
+        L.part_fw_elems[0] = (c.mode == REV_MODE_BF16) ? wgrad_partial_elems((int)M, (int)C, (int)(2 * C)) : 0;
+        L.part_fw_elems[1] = (c.mode == REV_MODE_BF16) ? wgrad_partial_elems((int)M, (int)C, (int)C) : 0;
+        L.part_fw[0] = take((L.part_fw_elems[0] > 0 ? L.part_fw_elems[0] : 64) * 4);
+        L.part_fw[1] = take((L.part_fw_elems[1] > 0 ? L.part_fw_elems[1] : 64) * 4);
+    }
     L.total = pos;
     return L;
 }
@@ -241,6 +295,7 @@ static int merge_check(const rev_merge_cfg* c) {
         set_error("merge cfg: every size must be positive"); return REV_EINVAL;
     }
     if (c->mode != REV_MODE_FP32 && c->mode != REV_MODE_BF16) { set_error("merge cfg: unknown mode"); return REV_EINVAL; }
+    if (c->fusion != REV_FUSION_AVERAGE && c->fusion != REV_FUSION_MLP) { set_error("merge cfg: unknown fusion"); return REV_EINVAL; }
     if (c->grid_h % (2 * c->window) != 0 || c->grid_w % (2 * c->window) != 0) {
         set_error("merge cfg: grid_h and grid_w must be multiples of 2*window"); return REV_EINVAL;
     }
@@ -271,13 +326,47 @@ struct MergeRunner {
     const T* gam() const { return params; }
     const T* bet() const { return params + 4 * C; }
     const T* W() const { return params + 8 * C; }
+    // fusion MLP, behind the patch-merging parameters: Wa [C, 2C], ba [C], Wb [C, C], bb [C]
+    int64_t off_wa() const { return (int64_t)8 * C + (int64_t)8 * C * C; }
+    int64_t off_ba() const { return off_wa() + (int64_t)2 * C * C; }
+    int64_t off_wb() const { return off_ba() + C; }
+    int64_t off_bb() const { return off_wb() + (int64_t)C * C; }
+    bool mlp() const { return c.fusion == REV_FUSION_MLP; }
+    int Mi() const { return 4 * Mo; }
+
+    // fusion by a small MLP: [X1 | X2] -> hidden (pre-activation h and a = gelu(h) are both kept) -> z0
+    int fuse_mlp(hipStream_t s, const float* X1, const float* X2) {
+        const int M = Mi();
+        {
+            const int64_t n4 = (int64_t)M * C / 4;
+            ProfScope ps(K_CONVERT, s, (double)n4 * 4 * 2 * (4 + sizeof(T)));
+            hipLaunchKernelGGL((concat2_kernel<T>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, X1, X2, at<T>(L.cat),
+                               (int64_t)M, C / 4);
+            REV_HIP(hipGetLastError());
+        }
+        Epi e = {}; e.kind = EPI_BIAS_GELU; e.out = at<T>(L.h); e.out2 = at<T>(L.a); e.bias = params + off_ba(); e.ldo = C; e.solo = true;
+        Epi f = {}; f.kind = EPI_BIAS; f.out = at<T>(L.z0); f.bias = params + off_bb(); f.ldo = C; f.solo = true;
+        if constexpr (kBf16) {
+            RC(gemm_nt_bf16(s, at<T>(L.cat), 2 * C, params + off_wa(), 2 * C, M, C, 2 * C, e));
+            return gemm_nt_bf16(s, at<T>(L.a), C, params + off_wb(), C, M, C, C, f);
+        } else {
+            RC(gemm_nt_f32(s, at<T>(L.cat), 2 * C, params + off_wa(), 2 * C, M, C, 2 * C, e));
+            return gemm_nt_f32(s, at<T>(L.a), C, params + off_wb(), C, M, C, C, f);
+        }
+    }
 
     int gather_ln(hipStream_t s, const float* X1, const float* X2) {
+        if (mlp()) RC(fuse_mlp(s, X1, X2));
         ProfScope ps(K_LN_FWD, s, (double)Mo * 4 * C * (8 + sizeof(T)));
         dim3 grid((Mo + 3) / 4), block(256);
+        const T* z0 = mlp() ? at<T>(L.z0) : nullptr;
         switch (pick_maxj(4 * C)) {
-#define CASE(J) case J: hipLaunchKernelGGL((merge_ln_fwd_kernel<T, T, J>), grid, block, 0, s, X1, X2, gam(), bet(), c.ln_eps, \
-                                           at<T>(L.n), at<float>(L.stats), g, Mo); break;
+#define CASE(J) case J:                                                                                                      \
+            if (mlp()) hipLaunchKernelGGL((merge_ln_fwd_kernel<T, T, J, true>), grid, block, 0, s, X1, X2, z0, gam(), bet(),   \
+                                          c.ln_eps, at<T>(L.n), at<float>(L.stats), g, Mo);                                    \
+            else hipLaunchKernelGGL((merge_ln_fwd_kernel<T, T, J, false>), grid, block, 0, s, X1, X2, z0, gam(), bet(),        \
+                                    c.ln_eps, at<T>(L.n), at<float>(L.stats), g, Mo);                                          \
+            break;
             CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(8) CASE(12) CASE(16) CASE(24) CASE(32)
 #undef CASE
             default: set_error("merge: d_in too large"); return REV_EINVAL;
@@ -319,8 +408,14 @@ struct MergeRunner {
             dim3 grid(nblk), block(256);
             const size_t shmem = (size_t)8 * C * sizeof(float);
             switch (pick_maxj(4 * C)) {
-#define CASE(J) case J: hipLaunchKernelGGL((merge_ln_bwd_kernel<T, T, J>), grid, block, shmem, s, at<T>(L.dn), X1, X2, \
-                                           at<float>(L.stats), gam(), dX1, dX2, at<float>(L.part_ln), g, Mo, rpb); break;
+#define CASE(J) case J:                                                                                                      \
+                if (mlp()) hipLaunchKernelGGL((merge_ln_bwd_kernel<T, T, J, true>), grid, block, shmem, s, at<T>(L.dn), X1, X2, \
+                                              at<T>(L.z0), at<float>(L.stats), gam(), dX1, dX2, at<T>(L.dz0),                  \
+                                              at<float>(L.part_ln), g, Mo, rpb);                                               \
+                else hipLaunchKernelGGL((merge_ln_bwd_kernel<T, T, J, false>), grid, block, shmem, s, at<T>(L.dn), X1, X2,     \
+                                        (const T*)nullptr, at<float>(L.stats), gam(), dX1, dX2, (T*)nullptr,                  \
+                                        at<float>(L.part_ln), g, Mo, rpb);                                                     \
+                break;
                 CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(8) CASE(12) CASE(16) CASE(24) CASE(32)
 #undef CASE
                 default: set_error("merge: d_in too large"); return REV_EINVAL;
@@ -329,8 +424,47 @@ struct MergeRunner {
         }
         // d gamma | d beta are adjacent in the packed layout
         segs[1] = {at<float>(L.part_ln), dparams, nullptr, (int64_t)8 * C, (int64_t)8 * C, (int64_t)8 * C, nblk};
-        if (segs[0].P > 0) return reduce_multi(s, segs, 2);
-        return reduce_multi(s, &segs[1], 1);
+        if (segs[0].P > 0) RC(reduce_multi(s, segs, 2));
+        else RC(reduce_multi(s, &segs[1], 1));
+        return mlp() ? fuse_mlp_backward(s, dX1, dX2, dparams) : REV_OK;
+    }
+
+    // dz0 (cotangent of the fused map) -> dX1, dX2 and the gradients of the fusion MLP; cat, h, a are those
+    // the forward half of this call left in the workspace
+    int fuse_mlp_backward(hipStream_t s, float* dX1, float* dX2, float* dparams) {
+        const int M = Mi();
+        T* dz0 = at<T>(L.dz0);
+        T* dh = at<T>(L.dh);
+        RedSeg segs[4];
+        int nseg = 0;
+        RedSeg wseg[2];
+        // output layer: db = column sums, dWb = dz0^T * a, da = dz0 * Wb, dh = da * gelu'(h)
+        RC(colsum<T>(s, dz0, C, M, C, dparams + off_bb(), at<float>(L.part_col[0]), &segs[nseg++]));
+        Epi e = {}; e.kind = EPI_GELU_BWD; e.out = dh; e.aux = at<T>(L.h); e.ldo = C; e.solo = true;
+        Epi x1 = {}; x1.kind = EPI_PLAIN_F32; x1.outf = dX1; x1.ldo = C; x1.solo = true;
+        Epi x2 = x1; x2.outf = dX2;
+        if constexpr (kBf16) {
+            RC(gemm_wgrad_bf16(s, dz0, C, at<T>(L.a), C, M, C, C, dparams + off_wb(), at<float>(L.part_fw[1]), L.part_fw_elems[1], &wseg[1]));
+            RC(gemm_nn_bf16(s, dz0, C, params + off_wb(), C, M, C, C, e));
+        } else {
+            RC(gemm_wgrad_f32(s, dz0, C, at<T>(L.a), C, M, C, C, dparams + off_wb(), nullptr, 0, &wseg[1]));
+            RC(gemm_nn_f32(s, dz0, C, params + off_wb(), C, M, C, C, e));
+        }
+        // hidden layer: db = column sums of dh, dWa = dh^T * [X1 | X2], [dX1 | dX2] = dh * Wa (one GEMM per half:
+        // the two streams' cotangents are separate buffers)
+        RC(colsum<T>(s, dh, C, M, C, dparams + off_ba(), at<float>(L.part_col[1]), &segs[nseg++]));
+        if constexpr (kBf16) {
+            RC(gemm_wgrad_bf16(s, dh, C, at<T>(L.cat), 2 * C, M, C, 2 * C, dparams + off_wa(), at<float>(L.part_fw[0]), L.part_fw_elems[0], &wseg[0]));
+            RC(gemm_nn_bf16(s, dh, C, params + off_wa(), 2 * C, M, C, C, x1));
+            RC(gemm_nn_bf16(s, dh, C, params + off_wa() + C, 2 * C, M, C, C, x2));
+        } else {
+            RC(gemm_wgrad_f32(s, dh, C, at<T>(L.cat), 2 * C, M, C, 2 * C, dparams + off_wa(), nullptr, 0, &wseg[0]));
+            RC(gemm_nn_f32(s, dh, C, params + off_wa(), 2 * C, M, C, C, x1));
+            RC(gemm_nn_f32(s, dh, C, params + off_wa() + C, 2 * C, M, C, C, x2));
+        }
+        for (int w = 0; w < 2; ++w)
+            if (wseg[w].P > 0) segs[nseg++] = wseg[w];
+        return reduce_multi(s, segs, nseg);
     }
 };
 
@@ -344,7 +478,8 @@ int rev_merge_check_cfg(const rev_merge_cfg* cfg) { return merge_check(cfg); }
 
 int64_t rev_merge_param_count(const rev_merge_cfg* cfg) {
     if (merge_check(cfg) != REV_OK) return REV_EINVAL;
-    return (int64_t)8 * cfg->d_in + (int64_t)8 * cfg->d_in * cfg->d_in;
+    const int64_t C = cfg->d_in;
+    return 8 * C + 8 * C * C + (cfg->fusion == REV_FUSION_MLP ? 3 * C * C + 2 * C : 0);
 }
 
 int64_t rev_merge_workspace_bytes(const rev_merge_cfg* cfg) {

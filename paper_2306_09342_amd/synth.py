@@ -129,24 +129,30 @@ def make_inputs(cfg: dict, seed: int = 0, batch: int | None = None):
 
 # Stage transitions of the hierarchical workloads (Sec. 3.4): between stage s and s+1 of a hierarchy the
 # token grid halves per side and the width doubles.  Seeded inputs only; no arithmetic of the block here.
-def merge_cfgs(hier: dict, image: int = 224, patch: int = 4, window: int = 7):
-    """One dict per transition of HIERARCHIES[...]: batch (images), grid_h, grid_w, window, d_in, mode."""
+def merge_cfgs(hier: dict, image: int = 224, patch: int = 4, window: int = 7, fusion: str = "average"):
+    """One dict per transition of HIERARCHIES[...]: batch (images), grid_h, grid_w, window, d_in, mode, fusion."""
     out = []
     for s, st in enumerate(hier["stages"][:-1]):
         side = image // patch >> s
         out.append(dict(batch=hier["images"], grid_h=side, grid_w=side, window=window, d_in=st["d_model"],
-                        mode=st["mode"], ln_eps=1e-5))
+                        mode=st["mode"], ln_eps=1e-5, fusion=fusion))
     return out
 
 
 def make_merge_params(mcfg: dict, seed: int = 0, perturb: bool = False) -> np.ndarray:
-    """Packed float32 parameters of one transition: ln_gamma[4C], ln_beta[4C], W[2C, 4C]."""
+    """Packed float32 parameters of one transition: ln_gamma[4C], ln_beta[4C], W[2C, 4C], and for
+    mcfg["fusion"] == "mlp" the fusion MLP's Wa[C, 2C], ba[C], Wb[C, C], bb[C] behind them."""
     C = mcfg["d_in"]
     rng = np.random.default_rng([seed, 31, C])
     g = 1.0 + (0.1 * rng.standard_normal(4 * C) if perturb else np.zeros(4 * C))
     b = 0.1 * rng.standard_normal(4 * C) if perturb else np.zeros(4 * C)
     w = _trunc_normal(rng, (2 * C, 4 * C), 0.02)
-    flat = np.concatenate([g, b, w.ravel()]).astype(np.float32)
+    parts = [g, b, w.ravel()]
+    if mcfg.get("fusion", "average") == "mlp":
+        # fusion MLP (Sec. 3.4): Wa[C, 2C], ba[C], Wb[C, C], bb[C], drawn like the blocks' linear maps
+        parts += [_trunc_normal(rng, (C, 2 * C), 0.02).ravel(), 0.02 * rng.standard_normal(C) if perturb else np.zeros(C),
+                  _trunc_normal(rng, (C, C), 0.02).ravel(), 0.02 * rng.standard_normal(C) if perturb else np.zeros(C)]
+    flat = np.concatenate(parts).astype(np.float32)
     if mcfg.get("mode", "fp32") == "bf16":
         flat = to_bf16_grid(flat)
     return flat

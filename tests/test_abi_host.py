@@ -152,6 +152,11 @@ def test_merge_cfg_validation_and_sizes():
     ok = B.make_merge_cfg(4, 56, 56, 7, 96, "bf16")
     assert B.rev_merge_check_cfg(ok) == 0
     assert B.rev_merge_param_count(ok) == 8 * 96 + 8 * 96 * 96
+    mlp = B.make_merge_cfg(4, 56, 56, 7, 96, "bf16", fusion="mlp")
+    assert B.rev_merge_check_cfg(mlp) == 0
+    assert B.rev_merge_param_count(mlp) == 8 * 96 + 8 * 96 * 96 + 3 * 96 * 96 + 2 * 96
+    assert B.rev_merge_workspace_bytes(mlp) > B.rev_merge_workspace_bytes(ok)
+    assert B.rev_merge_check_cfg(B.make_merge_cfg(4, 56, 56, 7, 96, "bf16", fusion=2)) < 0
     # the workspace holds at least the normalised rows, the statistics and the two activation-typed cotangents
     mo = 4 * 28 * 28
     assert B.rev_merge_workspace_bytes(ok) >= mo * (4 * 96 * 2 * 2 + 2 * 96 * 2 + 8)

@@ -29,6 +29,16 @@ CASES = {
 }
 
 
+# the small-MLP choice of the stream fusion: narrow and wide, both modes, K of the hidden layer not a multiple of 64
+MLP_CASES = {
+    "mlp_tiny_fp32": dict(batch=2, grid_h=8, grid_w=4, window=2, d_in=8, mode="fp32", ln_eps=1e-5, fusion="mlp"),
+    "mlp_windows7_bf16": dict(batch=2, grid_h=28, grid_w=14, window=7, d_in=96, mode="bf16", ln_eps=1e-5, fusion="mlp"),
+    "mlp_width192_bf16": dict(batch=5, grid_h=28, grid_w=28, window=7, d_in=192, mode="bf16", ln_eps=1e-6, fusion="mlp"),
+    "mlp_width384_fp32": dict(batch=1, grid_h=14, grid_w=28, window=7, d_in=384, mode="fp32", ln_eps=1e-5, fusion="mlp"),
+    "mlp_wide_bf16": dict(batch=1, grid_h=14, grid_w=14, window=7, d_in=768, mode="bf16", ln_eps=1e-5, fusion="mlp"),
+}
+
+
 def _run(mcfg, seed):
     flat = synth.make_merge_params(mcfg, seed=seed, perturb=True)
     X1, X2, dA, dB = synth.make_merge_inputs(mcfg, seed=seed)
@@ -62,6 +72,29 @@ def test_merge_matches_the_oracle(name):
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, (name, bad)
     assert torch.equal(res["dX1"], res["dX2"]), "both streams receive the same cotangent"
+
+
+@pytest.mark.parametrize("name", list(MLP_CASES))
+def test_merge_with_mlp_fusion_matches_the_oracle(name):
+    mcfg = MLP_CASES[name]
+    print(f"[case] merge {name} {mcfg}", flush=True)
+    flat, (X1, X2, dA, dB), out, res = _run(mcfg, seed=21)
+    g = (mcfg["batch"], mcfg["grid_h"], mcfg["grid_w"], mcfg["window"])
+    C = mcfg["d_in"]
+    assert flat.size == 8 * C + 8 * C * C + 3 * C * C + 2 * C
+    r_out = MO.merge_forward(X1, X2, flat, *g, eps=mcfg["ln_eps"])
+    r_dX1, r_dX2, r_dp = MO.merge_backward(X1, X2, dA, dB, flat, *g, eps=mcfg["ln_eps"])
+    assert set(r_dp) == {"ln_g", "ln_b", "w", "fa_w", "fa_b", "fb_w", "fb_b"}
+    tol = TOL[mcfg["mode"]]
+    got_dp = MO.unpack_params(res["dparams"].cpu().numpy(), C)
+    errs = {"out": rel_err(out.cpu().numpy(), r_out), "dX1": rel_err(res["dX1"].cpu().numpy(), r_dX1),
+            "dX2": rel_err(res["dX2"].cpu().numpy(), r_dX2)}
+    for k in r_dp:
+        errs["d" + k] = rel_err(got_dp[k], r_dp[k])
+    print("[ok] " + " ".join(f"{k} {v:.2e}" for k, v in errs.items()), flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (name, bad)
+    assert not torch.equal(res["dX1"], res["dX2"]), "the MLP treats the two streams differently"
 
 
 def test_two_calls_give_the_same_bits():
