@@ -627,13 +627,14 @@ int attention_forward<float>(hipStream_t s, const float* qkv, float* o, float* l
 template <>
 int attention_backward<bf16>(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse,
                              bf16* dqkv, float* delta, int B, int T, int H, int dh, const int* key_len, bool solo) {
-    if ((dh & 7) || dh > 128 || !mfma_ok(qkv, o, dout, dqkv))
+    // Heads wider than 96 take the plain-ALU kernels: the matrix-core dK/dV kernel would need more registers
+    // than a wavefront has for a 128-wide head (it spilled), and no workload of the path has such heads.
+    if ((dh & 7) || dh > 96 || !mfma_ok(qkv, o, dout, dqkv))
         return attention_backward_simple<bf16>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len);
     ProfScope ps(K_ATTN_BWD, s, 8.0 * B * H * (double)T * T * dh);
     if (dh <= 32) return bwd_launch<32>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
     if (dh <= 64) return bwd_launch<64>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
-    if (dh <= 96) return bwd_launch<96>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
-    return bwd_launch<128>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
+    return bwd_launch<96>(s, qkv, o, dout, lse, dqkv, delta, B, T, H, dh, key_len, solo);
 }
 template <>
 int attention_backward<float>(hipStream_t s, const float* qkv, const float* o, const float* dout, const float* lse,
