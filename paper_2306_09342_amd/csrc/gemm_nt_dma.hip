@@ -118,7 +118,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     // product groups of the current one, so the matrix cores start right after the barrier.
     constexpr bool SPREAD = (NW == 4 && TM * TN >= 16 && NS == 2 && LPW % (BK / 16) == 0);
     // 64x64 per wavefront (four wavefronts, the default 128x128 tile) or 160x64 (two wavefronts, the tall tile)
-    constexpr bool HANDPLACED_SHAPE = (((TM == 2 && (NW == 4 || NW == 2)) || (TM == 5 && NW == 2) || (TM == 4 && NW == 8)) && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
+    constexpr bool HANDPLACED_SHAPE = (((TM == 2 && (NW == 4 || NW == 2)) || (TM == 5 && NW == 2)) && TN == 2 && BK == 64 && NS == 2 && !SPREAD);
 
     // Epilogue geometry (a wavefront's 32-row panels leave through LDS in full rows) and, for the
     // epilogues that read a second operand (residual stream, saved pre-activation), that operand:
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
     const int n = n0 + wn * CW + 4 * c4;
     // (float32 residual rows cost 4 registers each: only the first panel's are held across the main
     // loop, the second panel's are requested when the epilogue starts)
-    constexpr int PRE = (!HANDPLACED_SHAPE || TM == 4) ? 0 : (KIND == EPI_GELU_BWD ? (TM > 2 ? 2 : TM) : (KIND == EPI_RESIDUAL ? 1 : 0));
+    constexpr int PRE = !HANDPLACED_SHAPE ? 0 : (KIND == EPI_GELU_BWD ? (TM > 2 ? 2 : TM) : (KIND == EPI_RESIDUAL ? 1 : 0));
     f32x4_t opnd_pre[TM][NP];
     if (PRE > 0 && n < N) {
 #pragma unroll
@@ -198,23 +198,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
                 dma16_sbase((NW * t) < IA ? ak : bk, voff[t], sbase + dst[t]);
         };
         auto stage_body = [&](auto stage_tag, auto next_tag, int kt) {
-            // the stage offset rides in the instruction's 16-bit offset field where the whole ring fits it;
-            // larger rings add it to the address registers
-            constexpr bool BIG_RING = NS * STAGE > 65536;
-            constexpr int SOFF = BIG_RING ? 0 : decltype(stage_tag)::value * STAGE;
-            constexpr unsigned SADD = BIG_RING ? decltype(stage_tag)::value * STAGE : 0;
+            // the stage offset rides in the instruction's 16-bit offset field
+            constexpr int SOFF = decltype(stage_tag)::value * STAGE;
+            static_assert(SOFF + (TM - 1) * 32 * ROWB < 65536 && SOFF + 3 * 16 * 256 + 4 * 256 < 65536, "LDS read offsets are 16 bits wide");
             constexpr bool has_next = decltype(next_tag)::value;
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __builtin_amdgcn_s_barrier();
             u32x4_t a[4][TM], b[4][2];
             auto read_group = [&](auto kk_tag) {
                 constexpr int kk = decltype(kk_tag)::value;
-                a[kk][0] = lds_read_b128(a_addr[kk] + SADD, SOFF);
-                a[kk][1] = lds_read_b128(a_addr[kk] + SADD, SOFF + 32 * ROWB);
-                if constexpr (TM == 4) {
-                    a[kk][2] = lds_read_b128(a_addr[kk] + SADD, SOFF + 64 * ROWB);
-                    a[kk][3] = lds_read_b128(a_addr[kk] + SADD, SOFF + 96 * ROWB);
-                }
+                a[kk][0] = lds_read_b128(a_addr[kk], SOFF);
+                a[kk][1] = lds_read_b128(a_addr[kk], SOFF + 32 * ROWB);
                 if constexpr (TM == 5) {
                     a[kk][2] = lds_read_b128(a_addr[kk], SOFF + 64 * ROWB);
                     a[kk][3] = lds_read_b128(a_addr[kk], SOFF + 96 * ROWB);
@@ -226,8 +220,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
                         b[kk][j] = join64(lds_read_tr16_b64(bt_addr[j], SOFF + kk * 16 * 256),
                                           lds_read_tr16_b64(bt_addr[j], SOFF + kk * 16 * 256 + 4 * 256));
                 } else {
-                    b[kk][0] = lds_read_b128(b_addr[kk] + SADD, SOFF);
-                    b[kk][1] = lds_read_b128(b_addr[kk] + SADD, SOFF + 32 * ROWB);
+                    b[kk][0] = lds_read_b128(b_addr[kk], SOFF);
+                    b[kk][1] = lds_read_b128(b_addr[kk], SOFF + 32 * ROWB);
                 }
             };
             auto products = [&](int kk) {
@@ -240,8 +234,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_dma_kernel(const bf16* _
             // waits until at most N younger LDS reads are outstanding; carries step kk's fragments
             auto wait_group = [&](auto n_tag, int kk) {
                 constexpr int N = decltype(n_tag)::value;
-                if constexpr (TM == 4) lds_wait6<N>(a[kk][0], a[kk][1], a[kk][2], a[kk][3], b[kk][0], b[kk][1]);
-                else if constexpr (TM == 5) lds_wait7<N>(a[kk][0], a[kk][1], a[kk][2], a[kk][3], a[kk][4], b[kk][0], b[kk][1]);
+                if constexpr (TM == 5) lds_wait7<N>(a[kk][0], a[kk][1], a[kk][2], a[kk][3], a[kk][4], b[kk][0], b[kk][1]);
                 else lds_wait4<N>(a[kk][0], a[kk][1], b[kk][0], b[kk][1]);
             };
             using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;

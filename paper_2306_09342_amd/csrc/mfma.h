@@ -79,16 +79,9 @@ __device__ __forceinline__ u32x2_t lds_read_tr16_b64(unsigned addr, int imm) {
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(imm) : "memory");
     return r;
 }
-__device__ __forceinline__ void lds_write_b32(unsigned addr, unsigned v) {
-    asm volatile("ds_write_b32 %0, %1" :: "v"(addr), "v"(v) : "memory");
-}
 template <int N>
 __device__ __forceinline__ void lds_wait4(u32x4_t& a0, u32x4_t& a1, u32x4_t& b0, u32x4_t& b1) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1) : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void lds_wait6(u32x4_t& a0, u32x4_t& a1, u32x4_t& a2, u32x4_t& a3, u32x4_t& b0, u32x4_t& b1) {
-    asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(b0), "+v"(b1) : "n"(N));
 }
 template <int N>
 __device__ __forceinline__ void lds_wait7(u32x4_t& a0, u32x4_t& a1, u32x4_t& a2, u32x4_t& a3, u32x4_t& a4, u32x4_t& b0,
