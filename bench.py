@@ -444,6 +444,49 @@ def main():
             e1.record()
             torch.cuda.synchronize()
             res[name] = work / (e0.elapsed_time(e1) / 10 * 1e-3)
+        del src, dst, a, b
+        # the same library on the GEMM shapes of this workload (plain products: no bias, GELU, residual or
+        # column sums, which the path's kernels fuse), aggregated like the kernel families above:
+        # total flops / total time of one block's launches
+        M, D, Dm = cfg["batch"] * cfg["seq_len"], cfg["d_model"], cfg["d_mlp"]
+        bf = dict(device="cuda", dtype=torch.bfloat16)
+
+        def lib_family(shapes, make):
+            t_us, fl = 0.0, 0.0
+            for N, K in shapes:
+                fn = make(N, K)
+                for _ in range(3):
+                    fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                t_us += e0.elapsed_time(e1) / 10 * 1e3
+                fl += 2.0 * M * N * K
+            return fl / t_us * 1e-6
+
+        def nt(N, K):          # activations [M, K] x weights [N, K]^T
+            x, w = torch.randn(M, K, **bf), torch.randn(N, K, **bf)
+            return lambda: torch.matmul(x, w.t())
+
+        def nn(N, K):          # output cotangents [M, K] x weights [K, N]
+            x, w = torch.randn(M, K, **bf), torch.randn(K, N, **bf)
+            return lambda: torch.matmul(x, w)
+
+        def tn(N, K):          # weight gradient [N, K] = cotangents [M, N]^T x activations [M, K]
+            g, x = torch.randn(M, N, **bf), torch.randn(M, K, **bf)
+            return lambda: torch.matmul(g.t(), x)
+
+        fwd = [(3 * D, D), (D, D), (Dm, D), (D, Dm)]                 # qkv, proj, fc1, fc2
+        bwd = [(D, 3 * D), (D, D), (D, Dm), (Dm, D)]                 # their input gradients
+        t_nt, t_nn = lib_family(fwd, nt), lib_family(bwd, nn)
+        res["library_gemm_workload_shapes_TFLOPs"] = {
+            "activation_products": t_nt, "input_gradients": t_nn, "weight_gradients": lib_family(fwd, tn),
+            "note": "torch.matmul (vendor library) on this workload's own GEMM shapes, plain products without the "
+                    "epilogues the path's kernels fuse; compare with kernel_families gemm_nt (both of the first two) "
+                    "and gemm_wgrad"}
         return res
 
     peaks = measured_peaks()
