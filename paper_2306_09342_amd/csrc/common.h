@@ -123,7 +123,7 @@ int reduce_multi(hipStream_t s, const RedSeg* segs, int nseg);
 // ---- epilogue description shared by the GEMM launchers ----------------------------
 enum EpiKind {
     EPI_BIAS = 0,      // out = acc + bias[n]                               (out: act type)
-    EPI_BIAS_GELU,     // h = acc + bias[n]; out = h; out2 = gelu(h)        (act type)
+    EPI_BIAS_GELU,     // h = acc + bias[n]; out = h (skipped when out is null); out2 = gelu(h)   (act type)
     EPI_RESIDUAL,      // outf = res[m,n] + sign * (acc + bias[n])          (float32)
     EPI_GELU_BWD,      // out = acc * gelu'(aux[m,n])                       (act type)
     EPI_PLAIN,         // out = acc                                         (act type)

@@ -69,7 +69,7 @@ __device__ __forceinline__ f32x4_t epi_store4(const Epi& e, int m, int n, f32x4_
     if (KIND == EPI_BIAS) {
         st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
     } else if (KIND == EPI_BIAS_GELU) {
-        st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);
+        if (e.out != nullptr) st_bf16x4(reinterpret_cast<bf16*>(e.out) + idx, acc);   // the pre-activation is optional
         f32x4_t a;
 #pragma unroll
         for (int k = 0; k < 4; ++k) a[k] = acc[k] * gelu_cdf(acc[k]);

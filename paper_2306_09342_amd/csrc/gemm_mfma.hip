@@ -25,7 +25,7 @@ __device__ __forceinline__ void epi_store(const Epi& e, int m, int n, float acc,
         reinterpret_cast<bf16*>(e.out)[idx] = __float2bfloat16(acc + biasv);
     } else if (KIND == EPI_BIAS_GELU) {
         float h = acc + biasv;
-        reinterpret_cast<bf16*>(e.out)[idx] = __float2bfloat16(h);
+        if (e.out != nullptr) reinterpret_cast<bf16*>(e.out)[idx] = __float2bfloat16(h);
         reinterpret_cast<bf16*>(e.out2)[idx] = __float2bfloat16(gelu_f(h));
     } else if (KIND == EPI_RESIDUAL) {
         e.outf[idx] = e.res[idx] + e.sign * (acc + biasv);

@@ -283,10 +283,11 @@ struct Runner {
         Epi e = epi0(); e.kind = EPI_RESIDUAL; e.outf = out1; e.res = in1; e.bias = P(blk, T_BPROJ); e.sign = sign; e.ldo = D;
         return Ops<T>::nt(s, sl.o, D, P(blk, T_WPROJ), D, M, D, D, e);
     }
-    // out2 = in2 + sign * G(y1)
-    int g_branch(hipStream_t s, int blk, const float* y1, const Slot& sl, const float* in2, float* out2, float sign) {
+    // out2 = in2 + sign * G(y1); the pre-activation of the MLP is kept only where a backward step will read it
+    int g_branch(hipStream_t s, int blk, const float* y1, const Slot& sl, const float* in2, float* out2, float sign,
+                 bool keep_h = true) {
         RC((ln_forward<T, T>(s, y1, P(blk, T_LN2G), P(blk, T_LN2B), c.ln_eps, sl.n2, sl.st2, M, D)));
-        Epi e = epi0(); e.kind = EPI_BIAS_GELU; e.out = sl.h; e.out2 = sl.a; e.bias = P(blk, T_BFC1); e.ldo = Dm;
+        Epi e = epi0(); e.kind = EPI_BIAS_GELU; e.out = keep_h ? sl.h : nullptr; e.out2 = sl.a; e.bias = P(blk, T_BFC1); e.ldo = Dm;
         RC(Ops<T>::nt(s, sl.n2, D, P(blk, T_WFC1), D, M, Dm, D, e));
         Epi r = epi0(); r.kind = EPI_RESIDUAL; r.outf = out2; r.res = in2; r.bias = P(blk, T_BFC2); r.sign = sign; r.ldo = D;
         return Ops<T>::nt(s, sl.a, Dm, P(blk, T_WFC2), Dm, M, D, Dm, r);
@@ -297,7 +298,7 @@ struct Runner {
         Slot sl = slot(0);
         RC(f_pre(s, blk, x2, sl));
         RC(f_post(s, blk, sl, x1, y1, 1.f));
-        return g_branch(s, blk, y1, sl, x2, y2, 1.f);
+        return g_branch(s, blk, y1, sl, x2, y2, 1.f, false);
     }
 
     // R_i: (y1,y2) -> (x1,x2) and the slot of block blk

@@ -16,7 +16,7 @@ __device__ __forceinline__ void apply_epi(const Epi& e, int m, int n, float acc)
             break;
         case EPI_BIAS_GELU: {
             float h = acc + to_f(reinterpret_cast<const T*>(e.bias)[n]);
-            reinterpret_cast<T*>(e.out)[idx] = from_f<T>(h);
+            if (e.out != nullptr) reinterpret_cast<T*>(e.out)[idx] = from_f<T>(h);
             reinterpret_cast<T*>(e.out2)[idx] = from_f<T>(gelu_f(h));
             break;
         }
