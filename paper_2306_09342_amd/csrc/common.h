@@ -171,6 +171,23 @@ int gemm_wgrad_f32(hipStream_t s, const float* G, int64_t ldg, const float* A, i
 int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
                     int M, int N, int K, float* dW, float* partial, int64_t partial_elems, RedSeg* defer = nullptr);
 
+// Several weight gradients over the same M tokens in ONE launch (the four of a transformer block): together their
+// tiles fill the device, so the token range is cut into fewer pieces (none for Rev-ViT-B) than each would need alone.
+// segs[k] receives the deferred fixed-order reduction of item k's pieces (P == 0: nothing to reduce).
+constexpr int WGRAD_GROUP_MAX = 4;
+struct WgradItem {
+    const bf16* G; int64_t ldg;        // cotangent [M, N]
+    const bf16* A; int64_t lda;        // activation [M, K]
+    int N, K;
+    float* dW;                         // [N, K]
+    float* partial; int64_t partial_elems;   // scratch for the pieces (may be null / 0: then this item allows no cut)
+};
+// max_ranges > 0 caps the number of token ranges (1: never cut, whatever share of the device the tiles fill).
+int gemm_wgrad_bf16_group(hipStream_t s, const WgradItem* items, int count, int M, RedSeg* segs, int max_ranges = 0);
+// device-side description of the launch (gemm_wgrad_dma.hip)
+struct WgradProblem { const bf16* G; const bf16* A; float* out; int64_t ldg, lda, split_stride; int N, K, tile0; };
+struct WgradGroup { WgradProblem p[WGRAD_GROUP_MAX]; int count, tiles_total; };
+
 // plain vector-ALU flavours (also the fall-back for shapes the matrix-core kernels do not take)
 int gemm_nt_bf16_simple(hipStream_t s, const bf16* A, int64_t lda, const bf16* B, int64_t ldb,
                         int M, int N, int K, const Epi& epi);

@@ -223,6 +223,7 @@ int64_t wgrad_partial_elems(int M, int N, int K) {
 
 int launch_wgrad_dma(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,
                      int S, int sps, float* out);
+int launch_wgrad_dma_group(hipStream_t s, WgradGroup grp, int M, int S, int sps);
 
 int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda,
                     int M, int N, int K, float* dW, float* partial, int64_t partial_elems, RedSeg* defer) {
@@ -249,6 +250,58 @@ int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, in
         return reduce_multi(s, &g, 1);
     }
     return REV_OK;
+}
+
+int gemm_wgrad_bf16_group(hipStream_t s, const WgradItem* items, int count, int M, RedSeg* segs, int max_ranges) {
+    bool fast = count >= 1 && count <= WGRAD_GROUP_MAX;
+    for (int k = 0; k < count && fast; ++k) {
+        const WgradItem& it = items[k];
+        if ((it.ldg & 7) || (it.lda & 7) || (it.N & 7) || (it.K & 7) || ((uintptr_t)it.G & 15) || ((uintptr_t)it.A & 15))
+            fast = false;
+    }
+    if (!fast) {                          // one at a time (any shape)
+        for (int k = 0; k < count; ++k) {
+            const WgradItem& it = items[k];
+            int rc = gemm_wgrad_bf16(s, it.G, it.ldg, it.A, it.lda, M, it.N, it.K, it.dW, it.partial, it.partial_elems, &segs[k]);
+            if (rc) return rc;
+        }
+        return REV_OK;
+    }
+    // token ranges: tiles of all items x S fills, but does not exceed, the 512 workgroup slots; at least 4 steps per
+    // range; no more ranges than every item's scratch holds
+    WgradGroup grp = {};
+    grp.count = count;
+    int tiles_total = 0;
+    double flops = 0;
+    for (int k = 0; k < count; ++k) {
+        grp.p[k].tile0 = tiles_total;
+        tiles_total += ((items[k].N + WG_BP - 1) / WG_BP) * ((items[k].K + WG_BQ - 1) / WG_BQ);
+        flops += 2.0 * M * items[k].N * items[k].K;
+    }
+    grp.tiles_total = tiles_total;
+    const int steps = (M + WG_BR - 1) / WG_BR;
+    int S = 512 / tiles_total;
+    if (S > steps / 4) S = steps / 4;
+    if (S > 128) S = 128;
+    if (max_ranges > 0 && S > max_ranges) S = max_ranges;
+    for (int k = 0; k < count; ++k) {
+        const int64_t cap = items[k].partial ? items[k].partial_elems / ((int64_t)items[k].N * items[k].K) : 0;
+        if (S > cap) S = (int)cap;
+    }
+    if (S < 1) S = 1;
+    const int sps = (steps + S - 1) / S;
+    S = (steps + sps - 1) / sps;                               // no empty ranges
+    for (int k = 0; k < count; ++k) {
+        const WgradItem& it = items[k];
+        const int64_t nk = (int64_t)it.N * it.K;
+        grp.p[k].G = it.G; grp.p[k].A = it.A; grp.p[k].ldg = it.ldg; grp.p[k].lda = it.lda;
+        grp.p[k].N = it.N; grp.p[k].K = it.K;
+        grp.p[k].out = S > 1 ? it.partial : it.dW;
+        grp.p[k].split_stride = nk;
+        segs[k] = {it.partial, it.dW, nullptr, nk, nk, nk, S > 1 ? S : 0};
+    }
+    ProfScope ps(K_GEMM_WGRAD, s, flops);
+    return launch_wgrad_dma_group(s, grp, M, S, sps);
 }
 
 }  // namespace rev

@@ -21,24 +21,20 @@ constexpr int WD_BP = 128, WD_BQ = 128, WD_BR = 64;
 constexpr int WD_TILE = WD_BR * 256;            // bytes of one operand tile
 constexpr int WD_STAGE = 2 * WD_TILE;
 
+// One 128 x 128 tile of dW over one token range: `tile` counts the tiles of this weight gradient, `split` its token
+// ranges (range `split` covers steps_per_split 64-token steps and goes to out + split * split_stride).
 template <int NS>
-__global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__ G, int64_t ldg,
-                                                        const bf16* __restrict__ A, int64_t lda,
-                                                        int M, int N, int K, int steps_per_split,
-                                                        float* __restrict__ out, int64_t split_stride) {
+__device__ __forceinline__ void wgrad_dma_tile(const bf16* __restrict__ G, int64_t ldg,
+                                               const bf16* __restrict__ A, int64_t lda,
+                                               int M, int N, int K, int steps_per_split,
+                                               float* __restrict__ out, int64_t split_stride, int tile, int split) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // scalar: M0 values need no lane read-out
     const int wp = wave >> 1, wq = wave & 1;                       // 2 x 2 wavefronts, 64 x 64 each
     const int tiles_q = (K + WD_BQ - 1) / WD_BQ;
     const int tiles = ((N + WD_BP - 1) / WD_BP) * tiles_q;
-    // Each XCD takes one contiguous run of the (token range, tile) order, token range slowest: an XCD
-    // then works on one or two token ranges and on a block of tiles inside them, so both operands are
-    // partitioned over the XCDs' L2s (with every XCD walking all ranges of its tiles, each of them read
-    // the whole of one operand).  The slow tile index is the one along the WIDER output dimension.
-    const int lin = xcd_remap(blockIdx.x, gridDim.x);
-    const int split = lin / tiles;
-    const int tile = lin - split * tiles;
+    // The slow tile index is the one along the WIDER output dimension.
     const int tiles_p = tiles / tiles_q;
     int tp, tq;
     if (K > N) { tq = tile / tiles_p; tp = tile - tq * tiles_p; }
@@ -213,6 +209,45 @@ __global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__
             }
         }
     }
+}
+
+// Each XCD takes one contiguous run of the (token range, tile) order, token range slowest: an XCD
+// then works on one or two token ranges and on a block of tiles inside them, so both operands are
+// partitioned over the XCDs' L2s (with every XCD walking all ranges of its tiles, each of them read
+// the whole of one operand).
+template <int NS>
+__global__ __launch_bounds__(256) void wgrad_dma_kernel(const bf16* __restrict__ G, int64_t ldg,
+                                                        const bf16* __restrict__ A, int64_t lda,
+                                                        int M, int N, int K, int steps_per_split,
+                                                        float* __restrict__ out, int64_t split_stride) {
+    const int tiles = ((N + WD_BP - 1) / WD_BP) * ((K + WD_BQ - 1) / WD_BQ);
+    const int lin = xcd_remap(blockIdx.x, gridDim.x);
+    const int split = lin / tiles;
+    wgrad_dma_tile<NS>(G, ldg, A, lda, M, N, K, steps_per_split, out, split_stride, lin - split * tiles, split);
+}
+
+// Several weight gradients over the same M tokens in one launch (the four of a transformer block): the tiles of all
+// of them form one list, so that together they fill the device where each alone would have to cut its token range
+// into pieces (and sum the pieces afterwards) to do so.
+template <int NS>
+__global__ __launch_bounds__(256) void wgrad_dma_group_kernel(WgradGroup grp, int M, int steps_per_split) {
+    const int lin = xcd_remap(blockIdx.x, gridDim.x);
+    const int split = lin / grp.tiles_total;
+    const int gt = lin - split * grp.tiles_total;
+    int pi = 0;
+#pragma unroll
+    for (int k = 1; k < WGRAD_GROUP_MAX; ++k)
+        if (k < grp.count && gt >= grp.p[k].tile0) pi = k;
+    const WgradProblem& q = grp.p[pi];
+    wgrad_dma_tile<NS>(q.G, q.ldg, q.A, q.lda, M, q.N, q.K, steps_per_split, q.out, q.split_stride, gt - q.tile0, split);
+}
+
+int launch_wgrad_dma_group(hipStream_t s, WgradGroup grp, int M, int S, int sps) {
+    static LdsLimit lim;
+    if (int rc = lim.ensure(reinterpret_cast<const void*>(wgrad_dma_group_kernel<2>), 2 * WD_STAGE)) return rc;
+    hipLaunchKernelGGL(wgrad_dma_group_kernel<2>, dim3(grp.tiles_total * S), dim3(256), 2 * WD_STAGE, s, grp, M, sps);
+    REV_HIP(hipGetLastError());
+    return REV_OK;
 }
 
 int launch_wgrad_dma(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, int64_t lda, int M, int N, int K,

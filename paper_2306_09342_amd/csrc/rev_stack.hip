@@ -385,6 +385,23 @@ struct Runner {
         if constexpr (kBf16) for (int w = 0; w < 4; ++w) pwg[w] = at<float>(L.part_wg[w]);
         T* gy1b = gy1_act(blk, o1);
         RedSeg segs[4];
+        if constexpr (kBf16) {
+            // all four in one launch: together their tiles fill the device without cutting the token range (or with
+            // fewer cuts), which saves the float32 pieces and most of their reduction
+            const WgradItem items[4] = {
+                {d2b, D, sl.a, Dm, D, Dm, G(blk, T_WFC2), pwg[0], L.part_wg_elems[0]},
+                {dhb, Dm, sl.n2, D, Dm, D, G(blk, T_WFC1), pwg[1], L.part_wg_elems[1]},
+                {gy1b, D, sl.o, D, D, D, G(blk, T_WPROJ), pwg[2], L.part_wg_elems[2]},
+                {dqkv, 3 * D, sl.n1, D, 3 * D, D, G(blk, T_WQKV), pwg[3], L.part_wg_elems[3]}};
+            if (ev) for (int k = 0; k < 4; ++k) REV_HIP(hipStreamWaitEvent(s, ev[k], 0));
+            RC(gemm_wgrad_bf16_group(s, items, 4, M, segs));
+            if (done_w2) REV_HIP(hipEventRecord(done_w2, s));
+            RedSeg live4[4];
+            int n4 = 0;
+            for (int w = 0; w < 4; ++w)
+                if (segs[w].P > 0) live4[n4++] = segs[w];
+            return reduce_multi(s, live4, n4);
+        }
         if (ev) REV_HIP(hipStreamWaitEvent(s, ev[0], 0));
         RC(Ops<T>::wgrad(s, d2b, D, sl.a, Dm, M, D, Dm, G(blk, T_WFC2), pwg[0], L.part_wg_elems[0], &segs[0]));
         if (done_w2) REV_HIP(hipEventRecord(done_w2, s));
