@@ -23,6 +23,7 @@ CASES = {
     "vit_s_slice": (dict(n_blocks=2, d_model=384, n_heads=6, d_mlp=1536, seq_len=197, batch=3), [150, 197, 64]),
     "window": (dict(n_blocks=2, d_model=96, n_heads=3, d_mlp=384, seq_len=49, batch=5), [49, 1, 32, 31, 48]),
     "dh80_T300": (dict(n_blocks=1, d_model=160, n_heads=2, d_mlp=160, seq_len=300, batch=2), [300, 130]),
+    "dh64_T256": (dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=256, batch=3), [256, 100, 193]),
     "T1024": (dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=1024, batch=2), [700, 65]),
 }
 

@@ -26,6 +26,11 @@ SHAPES = {
     # window-attention shaped stages (49 tokens, head_dim 32): narrow first stage, many-headed last stage
     "window_stage1": dict(n_blocks=2, d_model=96, n_heads=3, d_mlp=384, seq_len=49, batch=7),
     "window_stage4": dict(n_blocks=1, d_model=768, n_heads=24, d_mlp=3072, seq_len=49, batch=2),
+    # the largest head the one-workgroup attention backward takes (256 tokens, 8 wavefronts, 133 KB of LDS), a ragged
+    # length just below it, and the first length beyond it (two-kernel path again)
+    "dh64_T256": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=256, batch=2),
+    "dh64_T231": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=231, batch=1),
+    "dh64_T257": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=257, batch=1),
     # 1024 tokens: keys and values no longer fit the on-chip tile pair, the streamed attention path runs
     "T1024_dh64": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=1024, batch=1),
 }
