@@ -184,6 +184,9 @@ struct WgradItem {
 };
 // max_ranges > 0 caps the number of token ranges (1: never cut, whatever share of the device the tiles fill).
 int gemm_wgrad_bf16_group(hipStream_t s, const WgradItem* items, int count, int M, RedSeg* segs, int max_ranges = 0);
+// token ranges the group launch uses for these shapes (1: no pieces, no scratch); item k then needs ranges * N[k] * K[k]
+// floats of scratch
+int wgrad_group_ranges(int M, const int* N, const int* K, int count);
 // device-side description of the launch (gemm_wgrad_dma.hip)
 struct WgradProblem { const bf16* G; const bf16* A; float* out; int64_t ldg, lda, split_stride; int N, K, tile0; };
 struct WgradGroup { WgradProblem p[WGRAD_GROUP_MAX]; int count, tiles_total; };

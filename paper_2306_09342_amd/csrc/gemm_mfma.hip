@@ -252,6 +252,24 @@ int gemm_wgrad_bf16(hipStream_t s, const bf16* G, int64_t ldg, const bf16* A, in
     return REV_OK;
 }
 
+// Token ranges of a group launch: tiles of all items x S fills, but does not exceed, the 512 workgroup slots; at
+// least 4 steps per range; at most 64 MB of pieces per item.
+int wgrad_group_ranges(int M, const int* N, const int* K, int count) {
+    int tiles_total = 0;
+    for (int k = 0; k < count; ++k) tiles_total += ((N[k] + WG_BP - 1) / WG_BP) * ((K[k] + WG_BQ - 1) / WG_BQ);
+    const int steps = (M + WG_BR - 1) / WG_BR;
+    int S = 512 / (tiles_total > 0 ? tiles_total : 1);
+    if (S > steps / 4) S = steps / 4;
+    if (S > 128) S = 128;
+    for (int k = 0; k < count; ++k) {
+        const int64_t cap = ((int64_t)64 << 20) / ((int64_t)N[k] * K[k] * 4);
+        if (S > cap) S = (int)cap;
+    }
+    if (S < 1) S = 1;
+    const int sps = (steps + S - 1) / S;
+    return (steps + sps - 1) / sps;                            // no empty ranges
+}
+
 int gemm_wgrad_bf16_group(hipStream_t s, const WgradItem* items, int count, int M, RedSeg* segs, int max_ranges) {
     bool fast = count >= 1 && count <= WGRAD_GROUP_MAX;
     for (int k = 0; k < count && fast; ++k) {
@@ -280,9 +298,9 @@ int gemm_wgrad_bf16_group(hipStream_t s, const WgradItem* items, int count, int 
     }
     grp.tiles_total = tiles_total;
     const int steps = (M + WG_BR - 1) / WG_BR;
-    int S = 512 / tiles_total;
-    if (S > steps / 4) S = steps / 4;
-    if (S > 128) S = 128;
+    int Ns[WGRAD_GROUP_MAX], Ks[WGRAD_GROUP_MAX];
+    for (int k = 0; k < count; ++k) { Ns[k] = items[k].N; Ks[k] = items[k].K; }
+    int S = wgrad_group_ranges(M, Ns, Ks, count);
     if (max_ranges > 0 && S > max_ranges) S = max_ranges;
     for (int k = 0; k < count; ++k) {
         const int64_t cap = items[k].partial ? items[k].partial_elems / ((int64_t)items[k].N * items[k].K) : 0;

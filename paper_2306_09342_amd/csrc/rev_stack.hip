@@ -99,7 +99,6 @@ static int check_cfg(const rev_cfg* c) {
 // ---------------------------------------------------------------------------------
 // workspace layout (byte offsets, every region 256-byte aligned)
 // ---------------------------------------------------------------------------------
-int64_t wgrad_partial_elems(int M, int N, int K);   // gemm_mfma.hip
 
 struct Layout {
     int64_t slot[2];
@@ -176,10 +175,12 @@ static Layout make_layout(const rev_cfg& c, bool compact) {
         L.part_col[1] = take(e1 * 4);
     }
     if (c.mode == REV_MODE_BF16) {
-        // split-reduction scratch of the four weight gradients: fc2, fc1, proj, qkv
-        const int64_t nn[4] = {D, Dm, D, 3 * D}, kk[4] = {Dm, D, D, D};
+        // scratch for the pieces of the four weight gradients (fc2, fc1, proj, qkv), which go out as one launch: none
+        // where their tiles fill the device without cutting the token range
+        const int nn[4] = {(int)D, (int)Dm, (int)D, (int)(3 * D)}, kk[4] = {(int)Dm, (int)D, (int)D, (int)D};
+        const int S = wgrad_group_ranges((int)M, nn, kk, 4);
         for (int w = 0; w < 4; ++w) {
-            L.part_wg_elems[w] = wgrad_partial_elems((int)M, (int)nn[w], (int)kk[w]);
+            L.part_wg_elems[w] = S > 1 ? (int64_t)S * nn[w] * kk[w] : 0;
             L.part_wg[w] = take((L.part_wg_elems[w] > 0 ? L.part_wg_elems[w] : 64) * 4);
         }
     }
