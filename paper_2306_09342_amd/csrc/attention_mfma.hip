@@ -111,8 +111,8 @@ __device__ __forceinline__ void store4_bf16(bf16* p, float a, float b, float c, 
     *reinterpret_cast<bf16x4_t*>(p) = v;
 }
 
-// ---- resident mode (64-wide heads) ---------------------------------------------------------------------
-// The streamed operands of a whole head are requested at once with direct-to-LDS loads, tile by tile, and a
+// ---- helpers of the one-workgroup backward kernel (64-wide heads) -----------------------------------------
+// The operands of a whole head are requested at once with direct-to-LDS loads, tile by tile, and a
 // 64-row tile is consumed as soon as its own loads have landed: one memory latency per workgroup instead of one
 // per tile.  LDS rows are dense (128 B); the 16-byte chunk c of row r sits at position c ^ rsw(r), which serves
 // both access patterns without padding: 16 consecutive rows of one chunk (operand fragments read row-wise) hit 16
@@ -176,7 +176,8 @@ __device__ __forceinline__ void res_request(unsigned char* d0, const bf16* b0, i
     for (int j = 0; j < 4; ++j) rem[j] = total - issued[j];
     total_out = total;
 }
-// waits until at most n (wavefront-uniform, even, at most 14) vector-memory loads of the wavefront are outstanding
+// waits until at most n (wavefront-uniform, even, at most 16; anything else waits for all) vector-memory loads of the
+// wavefront are outstanding
 __device__ __forceinline__ void res_wait(int n) {
     switch (n) {
         case 0: __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0)); break;
