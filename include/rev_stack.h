@@ -153,8 +153,9 @@ int rev_stack_backward_reprop(const rev_cfg* cfg, const void* params,
  * V_i waits for R_i, and R_{i-2} waits for V_i (which frees the activation
  * slot it will overwrite), so R_{i-1} overlaps V_i.  Within V_i only the
  * input-gradient kernels (the part V_{i-1} depends on) stay on `stream_grad`;
- * its four weight-gradient GEMMs follow R_{i-1} on `stream_recompute`, each
- * ordered after the kernel that produces its cotangent operand.
+ * its four weight-gradient GEMMs follow R_{i-1} on `stream_recompute` (in bf16
+ * mode as one launch, ordered after the kernels that produce their cotangent
+ * operands; in float32 mode one by one, each after its own).
  * `stream_recompute` first
  * waits for everything already enqueued on `stream_grad` and is joined back
  * into `stream_grad` before the call returns.  The two streams must differ and
