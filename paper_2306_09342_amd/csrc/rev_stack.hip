@@ -438,7 +438,8 @@ struct Runner {
     //   D_i  after W_{i+2}                  (dh/dqkv/gY1 buffers of the same parity are free again)
     //   D_i  after the fc2 weight gradient of W_{i+1}   (it reads the dY2 copy that D_i's last kernel rewrites)
     //   R_i  after D_{i+2}                  (slot i mod 2 and ring level i+2 are free; W_{i+2} precedes R_i on sr)
-    //   each GEMM of W_i after the kernel of D_i that produces its cotangent operand
+    //   W_i after the kernels of D_i that produce its cotangent operands (bf16 mode: one launch for the four GEMMs,
+    //   so after all of them; float32 mode: each GEMM after its own)
     // and sv finally waits for W_1, so everything is ordered before later work on sv.
     int backward(int schedule, const float* Y1, const float* Y2, const float* dY1, const float* dY2,
                  float* dX1, float* dX2, float* X1o, float* X2o, hipStream_t sv, hipStream_t sr) {
