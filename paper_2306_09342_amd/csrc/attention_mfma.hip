@@ -12,10 +12,9 @@
 // row-major LDS tile with the LDS transpose read.  No tile is ever transposed
 // through memory or shuffled across lanes.
 //
-// 64-wide heads of up to 256 tokens run both backward passes in ONE workgroup per head (attn_bwd_fused64) when the
-// launch has the device to itself: Q, K, V and dO of the head go to LDS once, with direct-to-LDS loads, and the row
-// statistics travel from pass 1 to pass 2 through LDS.  Other shapes, and launches that share the device with
-// another stream, use the two kernels.
+// 64-wide heads of up to 256 tokens run both backward passes in ONE workgroup per head (attn_bwd_fused64): Q, K, V
+// and dO of the head go to LDS once, with direct-to-LDS loads, and the row statistics travel from pass 1 to pass 2
+// through LDS.  Other shapes use the two kernels.
 #include "mfma.h"
 
 namespace rev {
@@ -895,12 +894,11 @@ static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B
 template <int DHP>
 static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse, bf16* dqkv,
                       float* delta, int B, int T, int H, int dh, const int* key_len, bool solo) {
-    // 64-wide heads of up to 256 tokens, single-stream launches: one workgroup per head runs both passes from one LDS
-    // copy of the head (14-20 % faster than the two kernels at 197 tokens, 40 % at 49; same arithmetic in the same
-    // order, so the same bits).  Next to another stream's kernels its 116 KB of LDS keep the neighbour off the CU
-    // (measured on one box: parallel schedule 2-3 % slower with it, sequential 1.5 % faster), so there the two
-    // kernels stay.
-    if (solo && DHP == 64 && dh == 64 && T <= 256) {
+    // 64-wide heads of up to 256 tokens: one workgroup per head runs both passes from one LDS copy of the head
+    // (14-20 % faster than the two kernels at 197 tokens, 40 % at 49; same arithmetic in the same order, so the same
+    // bits).  Under both schedules: A/B on two boxes, the parallel schedule gains 3.7 % from it on Rev-ViT-B and
+    // 4.6 % on Rev-ViT-S, the sequential one 1.5 %.
+    if (DHP == 64 && dh == 64 && T <= 256) {
         const int tiles = (T + 31) / 32;
         const size_t shmem = (size_t)tiles * 32 * (4 * 128 + 8);
         RC_LDS(raise_lds(attn_bwd_fused64, shmem));
@@ -910,13 +908,13 @@ static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16*
     }
     int nblk, nw;
     row_split(T, &nblk, &nw);
-    // A launch that has the device to itself splits a head's row tiles over 4-wavefront workgroups:
-    // the backward kernels need 160-210 registers, so only one 7-wavefront workgroup fits a CU but
-    // three (two) of 4 wavefronts do -- 4 % (197 tokens) to 12 % (257 tokens) faster.  Next to another
-    // stream's kernels the extra resident workgroups cost the neighbour more than they gain (measured:
-    // PaReprop 2 % slower), so there one workgroup per head stays.  A wavefront's work does not depend
-    // on the grouping, so the results are bit-identical.
-    if (solo && nw > 4) {
+    // A head's row tiles are split over 4-wavefront workgroups: the backward kernels need 160-210 registers, so only
+    // one 5...8-wavefront workgroup fits a CU but three (two) of 4 wavefronts do -- 4 % (197 tokens) to 12 % (257
+    // tokens) faster alone.  Next to another stream's kernels the extra resident workgroups cost the neighbour; measured
+    // in the parallel schedule: 257 tokens (9 row tiles) +1.9 % with the split, 512 tokens (16 row tiles) -0.7 %, so
+    // there it is taken up to 12 row tiles.  A wavefront's work does not depend on the grouping, so the results are
+    // bit-identical.
+    if ((solo || (T + 31) / 32 <= 12) && nw > 4) {
         nblk = ((T + 31) / 32 + 3) / 4;
         nw = 4;
     }
