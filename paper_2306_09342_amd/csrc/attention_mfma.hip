@@ -12,8 +12,8 @@
 // row-major LDS tile with the LDS transpose read.  No tile is ever transposed
 // through memory or shuffled across lanes.
 //
-// 64-wide heads of up to 256 tokens run both backward passes in ONE workgroup per head (attn_bwd_fused64): Q, K, V
-// and dO of the head go to LDS once, with direct-to-LDS loads, and the row statistics travel from pass 1 to pass 2
+// Heads of 64 or 32 features and up to 256 tokens run both backward passes in ONE workgroup per head
+// (attn_bwd_fused): Q, K, V and dO of the head go to LDS once, with direct-to-LDS loads, and the row statistics travel from pass 1 to pass 2
 // through LDS.  Other shapes use the two kernels.
 #include "mfma.h"
 
@@ -110,21 +110,26 @@ __device__ __forceinline__ void store4_bf16(bf16* p, float a, float b, float c, 
     *reinterpret_cast<bf16x4_t*>(p) = v;
 }
 
-// ---- helpers of the one-workgroup backward kernel (64-wide heads) -----------------------------------------
+// ---- helpers of the one-workgroup backward kernel (heads of DH = 64 or 32 features) --------------------------
 // The operands of a whole head are requested at once with direct-to-LDS loads, tile by tile, and a
 // 64-row tile is consumed as soon as its own loads have landed: one memory latency per workgroup instead of one
-// per tile.  LDS rows are dense (128 B); the 16-byte chunk c of row r sits at position c ^ rsw(r), which serves
-// both access patterns without padding: 16 consecutive rows of one chunk (operand fragments read row-wise) hit 16
-// distinct bank groups, and the 8 rows x 64 B of a transpose read spread evenly over the banks.
-__device__ __forceinline__ int rsw(int r) {
+// per tile.  LDS rows are dense (2 * DH bytes); the 16-byte chunk c of row r sits at position c ^ rsw<DH>(r), which
+// serves both access patterns without padding: 16 consecutive rows of one chunk (operand fragments read row-wise)
+// hit 16 distinct bank groups, and the rows of a transpose read spread evenly over the banks (128-byte rows: 8 rows x
+// 64 B; 64-byte rows: 8 whole rows, contiguous).
+template <int DH> __device__ __forceinline__ int rsw(int r);
+template <> __device__ __forceinline__ int rsw<64>(int r) {
     const int p = (r >> 1) & 7;
     return ((p & 1) << 2) | (p >> 1);
 }
-// wavefront-wide load number i of a [nrows, ld] matrix with 64 columns: rows 8i .. 8i+7 (clamped to the last
-// row) to the dense tile at dst
+template <> __device__ __forceinline__ int rsw<32>(int r) { return (r >> 2) & 3; }
+// wavefront-wide load number i of a [nrows, ld] matrix with DH columns: rows RPL*i .. RPL*i + RPL-1 (RPL = 512 / DH
+// rows of 2 * DH bytes, clamped to the last row) to the dense tile at dst
+template <int DH>
 __device__ __forceinline__ void res_dma8(unsigned char* dst, const bf16* __restrict__ base, int64_t ld, int nrows, int i, int lane) {
-    const int row = i * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ rsw(row);
+    constexpr int CPR = DH / 8, RPL = 64 / CPR;
+    const int row = i * RPL + lane / CPR;
+    const int c = (lane % CPR) ^ rsw<DH>(row);
     const unsigned voff = (unsigned)(min(row, nrows - 1) * (int)ld * 2 + c * 16);
     dma16_sbase(base, voff, (unsigned)(uintptr_t)LDS_PTR(unsigned char, dst) + i * 1024);
 }
@@ -140,33 +145,38 @@ __device__ __forceinline__ float res_load4(const void* p) {
     asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
     return r;
 }
-// owned-row fragments of a 64-wide head: lane (r = l%32, g) takes X[row0 + r][16*ks + 8g .. +7], rows clamped
+// owned-row fragments of a head: lane (r = l%32, g) takes X[row0 + r][16*ks + 8g .. +7], rows clamped
+template <int KS>
 __device__ __forceinline__ void res_load_owned(const bf16* __restrict__ base, int64_t ld, int row0, int nrows, int lane,
-                                               u32x4_t (&frag)[4]) {
+                                               u32x4_t (&frag)[KS]) {
     const int r = min(row0 + (lane & 31), nrows - 1);
     const bf16* p = base + (int64_t)r * ld + 8 * (lane >> 5);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) frag[ks] = res_load16(p + 16 * ks);
+    for (int ks = 0; ks < KS; ++ks) frag[ks] = res_load16(p + 16 * ks);
 }
 __device__ __forceinline__ void res_pin(u32x4_t (&f)[4]) {
     asm volatile("" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
 }
+__device__ __forceinline__ void res_pin(u32x4_t (&f)[2]) { asm volatile("" : "+v"(f[0]), "+v"(f[1])); }
 __device__ __forceinline__ void res_pin(float& a) { asm volatile("" : "+v"(a)); }
-__device__ __forceinline__ void res_frags(const u32x4_t (&f)[4], bf16x8_t (&b)[4]) {
+template <int KS>
+__device__ __forceinline__ void res_frags(const u32x4_t (&f)[KS], bf16x8_t (&b)[KS]) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) b[ks] = as_bf16x8(f[ks]);
+    for (int ks = 0; ks < KS; ++ks) b[ks] = as_bf16x8(f[ks]);
 }
 // Requests rows [0, tp) of two matrices, 64-row tile by tile; returns through rem[j] how many of THIS wavefront's
 // loads are younger than those of tile j (what may still be outstanding when tile j is consumed).
+template <int DH>
 __device__ __forceinline__ void res_request(unsigned char* d0, const bf16* b0, int64_t ld0, unsigned char* d1, const bf16* b1,
                                             int64_t ld1, int nrows, int tp, int wave, int nw, int lane, int (&rem)[4], int& total_out) {
+    constexpr int RPL = 512 / DH, LPT = 64 / RPL;          // rows per wavefront-wide load, loads per 64-row tile
     int issued[4] = {0, 0, 0, 0}, total = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int i1 = min(8 * j + 8, tp >> 3);
-        for (int i = 8 * j + wave; i < i1; i += nw) {
-            res_dma8(d0, b0, ld0, nrows, i, lane);
-            res_dma8(d1, b1, ld1, nrows, i, lane);
+        const int i1 = min(LPT * j + LPT, tp / RPL);
+        for (int i = LPT * j + wave; i < i1; i += nw) {
+            res_dma8<DH>(d0, b0, ld0, nrows, i, lane);
+            res_dma8<DH>(d1, b1, ld1, nrows, i, lane);
             total += 2;
         }
         issued[j] = total;
@@ -192,13 +202,14 @@ __device__ __forceinline__ void res_wait(int n) {
     }
 }
 // per-lane byte offsets of the two transpose reads of tr_frag<4, 8> in a resident tile, for r0 = 0 (any r0 that is a
-// multiple of 16 adds r0 * 128) and feature tile dt
+// multiple of 16 adds r0 * 2 * DH) and feature tile dt
+template <int DH>
 __device__ __forceinline__ void res_tr_offsets(int lane, int dt, int& o1, int& o2) {
     const int j = lane & 15, q = lane >> 4;
     const int c = dt * 32 + (q & 1) * 16 + 4 * (j & 3);
     const int r = (q >> 1) * 4 + (j >> 2);
-    o1 = r * 128 + (((c >> 3) ^ rsw(r)) << 4) + (c & 7) * 2;
-    o2 = (r + 8) * 128 + (((c >> 3) ^ rsw(r + 8)) << 4) + (c & 7) * 2;
+    o1 = r * (2 * DH) + (((c >> 3) ^ rsw<DH>(r)) << 4) + (c & 7) * 2;
+    o2 = (r + 8) * (2 * DH) + (((c >> 3) ^ rsw<DH>(r + 8)) << 4) + (c & 7) * 2;
 }
 __device__ __forceinline__ bf16x8_t res_tr_frag(const unsigned char* tile_r0, int o1, int o2) {
     union { struct { s16x4_t lo, hi; } s; bf16x8_t v; } u;
@@ -626,23 +637,24 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_mfma(const bf16* __restrict_
 #define RES_BARRIER(n) do { asm volatile("" ::: "memory"); res_wait(n); __builtin_amdgcn_s_barrier(); asm volatile("" ::: "memory"); } while (0)
 
 // ----------------------------------------------------------------------------------------
-// backward, both passes in one workgroup per head (64-wide heads, up to 256 tokens): Q, K, V and dO of the head
+// backward, both passes in one workgroup per head (heads of DH = 64 or 32 features, up to 256 tokens): Q, K, V and dO of the head
 // are brought to LDS once; every wavefront first runs pass 1 for its 32 query rows (dQ, delta), then, after one
 // barrier, pass 2 for its 32 key rows (dK, dV) with the row statistics of pass 1 read from LDS.  Same arithmetic, in
 // the same order, as the two separate kernels; half their memory traffic.
 // ----------------------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+template <int DH>
+__global__ __launch_bounds__(512) void attn_bwd_fused(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                         const bf16* __restrict__ dout, const float* __restrict__ lse,
                                                         bf16* __restrict__ dqkv, float* __restrict__ delta,
                                                         const int* __restrict__ key_len, int T, int H) {
-    constexpr int KS = 4, DT = 2, dh = 64;
+    constexpr int KS = DH / 16, DT = DH / 32, dh = DH, ROWB = 2 * DH;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tp = (T + 31) / 32 * 32;               // == 32 * wavefronts of the workgroup
     unsigned char* Ks0 = smem;
-    unsigned char* Vs0 = Ks0 + tp * 128;
-    unsigned char* Qs0 = Vs0 + tp * 128;
-    unsigned char* Os0 = Qs0 + tp * 128;             // dO
-    float* lse_s0 = reinterpret_cast<float*>(Os0 + tp * 128);
+    unsigned char* Vs0 = Ks0 + tp * ROWB;
+    unsigned char* Qs0 = Vs0 + tp * ROWB;
+    unsigned char* Os0 = Qs0 + tp * ROWB;             // dO
+    float* lse_s0 = reinterpret_cast<float*>(Os0 + tp * ROWB);
     float* del_s0 = lse_s0 + tp;
     const int lane = threadIdx.x & 63, nw = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -660,29 +672,29 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
     const int Tk = key_len ? min(max(key_len[b], 1), T) : T;
     // ---- requests: owned rows of pass 1 to registers, then K and V (tile by tile), then Q and dO ----
     u32x4_t fq[KS], fdo[KS], fo[KS];
-    res_load_owned(base, ld, r0, T, lane, fq);
-    res_load_owned(dob, D, r0, T, lane, fdo);
-    res_load_owned(ob, D, r0, T, lane, fo);
+    res_load_owned<KS>(base, ld, r0, T, lane, fq);
+    res_load_owned<KS>(dob, D, r0, T, lane, fdo);
+    res_load_owned<KS>(ob, D, r0, T, lane, fo);
     float Lraw = res_load4(lse + (int64_t)bh * T + qc);
     int rem[4], nkv, nqo;
-    res_request(Ks0, base + D, ld, Vs0, base + 2 * D, ld, T, tp, wave, nw, lane, rem, nkv);
+    res_request<DH>(Ks0, base + D, ld, Vs0, base + 2 * D, ld, T, tp, wave, nw, lane, rem, nkv);
     {
         int rem2[4];
-        res_request(Qs0, base, ld, Os0, dob, D, T, tp, wave, nw, lane, rem2, nqo);
+        res_request<DH>(Qs0, base, ld, Os0, dob, D, T, tp, wave, nw, lane, rem2, nqo);
     }
     res_wait(min(nkv + nqo, 16));                    // the owned rows are older than every direct-to-LDS load
     res_pin(fq); res_pin(fdo); res_pin(fo); res_pin(Lraw);
 
     int rowoff[KS], o1[DT], o2[DT];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) rowoff[ks] = (lane & 31) * 128 + (((2 * ks + g) ^ rsw(lane & 31)) << 4);
+    for (int ks = 0; ks < KS; ++ks) rowoff[ks] = (lane & 31) * ROWB + (((2 * ks + g) ^ rsw<DH>(lane & 31)) << 4);
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) res_tr_offsets(lane, dt, o1[dt], o2[dt]);
+    for (int dt = 0; dt < DT; ++dt) res_tr_offsets<DH>(lane, dt, o1[dt], o2[dt]);
 
     // ---- pass 1: dQ, delta ----
     {
         bf16x8_t bq[KS], bdo[KS], bo[KS];
-        res_frags(fq, bq); res_frags(fdo, bdo); res_frags(fo, bo);
+        res_frags<KS>(fq, bq); res_frags<KS>(fdo, bdo); res_frags<KS>(fo, bo);
         const float L2 = Lraw * 1.4426950408889634f;
         float dl = 0.f;
 #pragma unroll
@@ -708,8 +720,8 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
             const int k0 = jt * 64;
             if (k0 < Tk) {
             RES_BARRIER(min(rem[jt] + nqo, 16));
-            const unsigned char* Ks = Ks0 + k0 * 128;
-            const unsigned char* Vs = Vs0 + k0 * 128;
+            const unsigned char* Ks = Ks0 + k0 * ROWB;
+            const unsigned char* Vs = Vs0 + k0 * ROWB;
             const int nt = (Tk - k0 > 32) ? 2 : 1;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -719,8 +731,8 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
                     for (int v = 0; v < 16; ++v) { aS[v] = 0.f; aP[v] = 0.f; }
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        aS = mfma32(*reinterpret_cast<const bf16x8_t*>(Ks + t * 32 * 128 + rowoff[ks]), bq[ks], aS);
-                        aP = mfma32(*reinterpret_cast<const bf16x8_t*>(Vs + t * 32 * 128 + rowoff[ks]), bdo[ks], aP);
+                        aS = mfma32(*reinterpret_cast<const bf16x8_t*>(Ks + t * 32 * ROWB + rowoff[ks]), bq[ks], aS);
+                        aP = mfma32(*reinterpret_cast<const bf16x8_t*>(Vs + t * 32 * ROWB + rowoff[ks]), bdo[ks], aP);
                     }
                     float ds[16];
                     if (k0 + t * 32 + 32 <= Tk) {
@@ -739,7 +751,7 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
                         const bf16x8_t dsb = pack8(&ds[8 * c]);
 #pragma unroll
                         for (int dt = 0; dt < DT; ++dt) {
-                            const bf16x8_t a = res_tr_frag(Ks + (t * 32 + 16 * c) * 128, o1[dt], o2[dt]);
+                            const bf16x8_t a = res_tr_frag(Ks + (t * 32 + 16 * c) * ROWB, o1[dt], o2[dt]);
                             accQ[dt] = mfma32(a, dsb, accQ[dt]);
                         }
                     }
@@ -767,8 +779,8 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
         bf16x8_t bk[KS], bv[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            bk[ks] = *reinterpret_cast<const bf16x8_t*>(Ks0 + r0 * 128 + rowoff[ks]);
-            bv[ks] = *reinterpret_cast<const bf16x8_t*>(Vs0 + r0 * 128 + rowoff[ks]);
+            bk[ks] = *reinterpret_cast<const bf16x8_t*>(Ks0 + r0 * ROWB + rowoff[ks]);
+            bv[ks] = *reinterpret_cast<const bf16x8_t*>(Vs0 + r0 * ROWB + rowoff[ks]);
         }
         f32x16_t accK[DT], accV[DT];
 #pragma unroll
@@ -777,8 +789,8 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
             for (int v = 0; v < 16; ++v) { accK[dt][v] = 0.f; accV[dt][v] = 0.f; }
 
         for (int i0 = 0; i0 < T; i0 += 64) {
-            const unsigned char* Qs = Qs0 + i0 * 128;
-            const unsigned char* Os = Os0 + i0 * 128;
+            const unsigned char* Qs = Qs0 + i0 * ROWB;
+            const unsigned char* Os = Os0 + i0 * ROWB;
             const float* lse_s = lse_s0 + i0;
             const float* del_s = del_s0 + i0;
             const int nt = (T - i0 > 32) ? 2 : 1;
@@ -790,8 +802,8 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
                     for (int v = 0; v < 16; ++v) { aS[v] = 0.f; aP[v] = 0.f; }
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        aS = mfma32(*reinterpret_cast<const bf16x8_t*>(Qs + t * 32 * 128 + rowoff[ks]), bk[ks], aS);
-                        aP = mfma32(*reinterpret_cast<const bf16x8_t*>(Os + t * 32 * 128 + rowoff[ks]), bv[ks], aP);
+                        aS = mfma32(*reinterpret_cast<const bf16x8_t*>(Qs + t * 32 * ROWB + rowoff[ks]), bk[ks], aS);
+                        aP = mfma32(*reinterpret_cast<const bf16x8_t*>(Os + t * 32 * ROWB + rowoff[ks]), bv[ks], aP);
                     }
                     float p[16], ds[16];
 #pragma unroll
@@ -814,9 +826,9 @@ __global__ __launch_bounds__(512) void attn_bwd_fused64(const bf16* __restrict__
                         const bf16x8_t dsb = pack8(&ds[8 * c]);
 #pragma unroll
                         for (int dt = 0; dt < DT; ++dt) {
-                            const bf16x8_t ao = res_tr_frag(Os + (t * 32 + 16 * c) * 128, o1[dt], o2[dt]);
+                            const bf16x8_t ao = res_tr_frag(Os + (t * 32 + 16 * c) * ROWB, o1[dt], o2[dt]);
                             accV[dt] = mfma32(ao, pb, accV[dt]);
-                            const bf16x8_t aq = res_tr_frag(Qs + (t * 32 + 16 * c) * 128, o1[dt], o2[dt]);
+                            const bf16x8_t aq = res_tr_frag(Qs + (t * 32 + 16 * c) * ROWB, o1[dt], o2[dt]);
                             accK[dt] = mfma32(aq, dsb, accK[dt]);
                         }
                     }
@@ -894,17 +906,19 @@ static int fwd_launch(hipStream_t s, const bf16* qkv, bf16* o, float* lse, int B
 template <int DHP>
 static int bwd_launch(hipStream_t s, const bf16* qkv, const bf16* o, const bf16* dout, const float* lse, bf16* dqkv,
                       float* delta, int B, int T, int H, int dh, const int* key_len, bool solo) {
-    // 64-wide heads of up to 256 tokens: one workgroup per head runs both passes from one LDS copy of the head
-    // (14-20 % faster than the two kernels at 197 tokens, 40 % at 49; same arithmetic in the same order, so the same
-    // bits).  Under both schedules: A/B on two boxes, the parallel schedule gains 3.7 % from it on Rev-ViT-B and
-    // 4.6 % on Rev-ViT-S, the sequential one 1.5 %.
-    if (DHP == 64 && dh == 64 && T <= 256) {
-        const int tiles = (T + 31) / 32;
-        const size_t shmem = (size_t)tiles * 32 * (4 * 128 + 8);
-        RC_LDS(raise_lds(attn_bwd_fused64, shmem));
-        hipLaunchKernelGGL(attn_bwd_fused64, dim3(B * H), dim3(tiles * 64), shmem, s, qkv, o, dout, lse, dqkv, delta, key_len, T, H);
-        REV_HIP(hipGetLastError());
-        return REV_OK;
+    // Heads of 64 or 32 features and up to 256 tokens: one workgroup per head runs both passes from one LDS copy of
+    // the head (14-20 % faster than the two kernels at 197 tokens, 40 % at 49; same arithmetic in the same order, so
+    // the same bits).  Under both schedules: A/B on two boxes, the parallel schedule gains 3.7 % from it on Rev-ViT-B
+    // and 4.6 % on Rev-ViT-S, the sequential one 1.5 %.
+    if constexpr (DHP == 64 || DHP == 32) {
+        if (dh == DHP && T <= 256) {
+            const int tiles = (T + 31) / 32;
+            const size_t shmem = (size_t)tiles * 32 * (4 * 2 * DHP + 8);
+            RC_LDS(raise_lds(attn_bwd_fused<DHP>, shmem));
+            hipLaunchKernelGGL(attn_bwd_fused<DHP>, dim3(B * H), dim3(tiles * 64), shmem, s, qkv, o, dout, lse, dqkv, delta, key_len, T, H);
+            REV_HIP(hipGetLastError());
+            return REV_OK;
+        }
     }
     int nblk, nw;
     row_split(T, &nblk, &nw);
