@@ -24,6 +24,7 @@ CASES = {
     "window": (dict(n_blocks=2, d_model=96, n_heads=3, d_mlp=384, seq_len=49, batch=5), [49, 1, 32, 31, 48]),
     "dh80_T300": (dict(n_blocks=1, d_model=160, n_heads=2, d_mlp=160, seq_len=300, batch=2), [300, 130]),
     "dh64_T256": (dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=256, batch=3), [256, 100, 193]),
+    "dh32_T130": (dict(n_blocks=1, d_model=64, n_heads=2, d_mlp=128, seq_len=130, batch=4), [130, 1, 64, 97]),
     "T1024": (dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=1024, batch=2), [700, 65]),
 }
 

@@ -31,6 +31,10 @@ SHAPES = {
     "dh64_T256": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=256, batch=2),
     "dh64_T231": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=231, batch=1),
     "dh64_T257": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=257, batch=1),
+    # 32-wide heads beyond one window: 7 wavefronts with a ragged tail, a single partial row tile, and the 256-token limit
+    "dh32_T200": dict(n_blocks=1, d_model=64, n_heads=2, d_mlp=128, seq_len=200, batch=2),
+    "dh32_T20": dict(n_blocks=2, d_model=64, n_heads=2, d_mlp=128, seq_len=20, batch=3),
+    "dh32_T256": dict(n_blocks=1, d_model=64, n_heads=2, d_mlp=128, seq_len=256, batch=1),
     # 1024 tokens: keys and values no longer fit the on-chip tile pair, the streamed attention path runs
     "T1024_dh64": dict(n_blocks=1, d_model=128, n_heads=2, d_mlp=128, seq_len=1024, batch=1),
 }
